@@ -1,0 +1,182 @@
+"""Mesh, computation layout, per-processor slices and einsum lowering (test infrastructure only).
+
+Sections "Hardware Assumptions" (mesh = n-dimensional array of processors, a naming
+abstraction), "Mesh-TensorFlow: Beyond Batch Splitting" (named dims; the computation
+layout is a partial map tensor-dim -> mesh-dim), "Tensor Representations" (a tensor's
+layout is the restriction of that map to its dims and must be injective; each mapped
+dim is cut down to the stripe of the processor's coordinate; sizes must divide evenly)
+and "Operation Implementation" (an einsum runs locally on the slices and is followed by
+an Allreduce over the mesh dims that reduced-out split dims map to).
+
+Readings taken where the text leaves a choice:
+  * a stripe is the contiguous block [c*n, (c+1)*n) for coordinate c;
+  * processors are numbered row-major over the mesh shape (last mesh dim fastest), which
+    is what makes one processor set viewable as [16,16,2], [32,16] or [512] by reshape;
+  * layout rules naming dims a tensor does not have are simply dropped (restriction);
+  * for an einsum, the union of its operands' dims is held to the same injectivity rule
+    as a single tensor: two different dims of one einsum on one mesh dim would make the
+    processors cover only diagonal blocks of the iteration space.
+
+A mesh is a list of (name, size); a layout is a list of (tensor_dim, mesh_dim).
+"""
+import itertools
+import numpy as np
+
+from .einsum import NT, einsum, union_dims, EinsumError
+
+
+class LayoutError(ValueError):
+    """code: DUP_DIM, DUP_RULE, UNKNOWN_MESH_DIM, LAYOUT_CONFLICT, INDIVISIBLE, COORD_RANGE."""
+
+    def __init__(self, code, msg=""):
+        super().__init__(f"{code}: {msg}")
+        self.code = code
+
+
+def mesh_size(mesh):
+    n = 1
+    for _, s in mesh:
+        n *= s
+    return n
+
+
+def rank_to_coord(mesh, rank):
+    if not 0 <= rank < mesh_size(mesh):
+        raise LayoutError("COORD_RANGE", f"rank {rank}")
+    coord = []
+    for _, s in reversed(mesh):
+        coord.append(rank % s)
+        rank //= s
+    return tuple(reversed(coord))
+
+
+def coord_to_rank(mesh, coord):
+    check_coord(mesh, coord)
+    rank = 0
+    for (_, s), c in zip(mesh, coord):
+        rank = rank * s + c
+    return rank
+
+
+def check_coord(mesh, coord):
+    if len(coord) != len(mesh):
+        raise LayoutError("COORD_RANGE", "length")
+    for (_, s), c in zip(mesh, coord):
+        if not 0 <= c < s:
+            raise LayoutError("COORD_RANGE", f"{c} not in [0,{s})")
+
+
+def check_mesh_and_layout(mesh, layout):
+    names = [n for n, _ in mesh]
+    if len(set(names)) != len(names):
+        raise LayoutError("DUP_DIM", "mesh dim names")
+    seen = set()
+    for tdim, mdim in layout:
+        if tdim in seen:                      # the layout is a map: one image per tensor dim
+            raise LayoutError("DUP_RULE", tdim)
+        seen.add(tdim)
+        if mdim not in names:
+            raise LayoutError("UNKNOWN_MESH_DIM", mdim)
+
+
+def tensor_layout(dims, mesh, layout):
+    """Restriction of the computation layout to `dims`: dict tensor_dim -> mesh axis index."""
+    check_mesh_and_layout(mesh, layout)
+    if len(set(dims)) != len(dims):
+        raise LayoutError("DUP_DIM", str(dims))
+    axis = {n: i for i, (n, _) in enumerate(mesh)}
+    restr, used = {}, {}
+    for tdim, mdim in layout:
+        if tdim in dims:
+            if mdim in used:
+                raise LayoutError("LAYOUT_CONFLICT", f"{used[mdim]} and {tdim} both on {mdim}")
+            used[mdim] = tdim
+            restr[tdim] = axis[mdim]
+    return restr
+
+
+def slice_spec(dims, sizes, mesh, layout, coord):
+    """(offsets, local sizes) of the slice the processor at `coord` holds."""
+    restr = tensor_layout(dims, mesh, layout)
+    check_coord(mesh, coord)
+    offs, locs = [], []
+    for d, n in zip(dims, sizes):
+        if d in restr:
+            parts = mesh[restr[d]][1]
+            if n % parts:
+                raise LayoutError("INDIVISIBLE", f"{d}={n} over {parts}")
+            loc = n // parts
+            offs.append(coord[restr[d]] * loc)
+            locs.append(loc)
+        else:
+            offs.append(0)
+            locs.append(n)
+    return tuple(offs), tuple(locs)
+
+
+def slice_tensor(t, mesh, layout, coord):
+    offs, locs = slice_spec(t.dims, t.data.shape, mesh, layout, coord)
+    idx = tuple(slice(o, o + n) for o, n in zip(offs, locs))
+    return NT(np.array(t.data[idx], order="C"), t.dims)
+
+
+def einsum_plan(in_dims, in_sizes, out_dims, mesh, layout):
+    """What the lowering of one einsum needs to know, from names and sizes alone.
+
+    Returns dict: union (name->size), reduced (names summed out), reduce_axes (sorted mesh
+    axes the partial results must be summed over), local sizes of every operand and of the
+    output, flops_global and flops_local.
+    """
+    sizes = {}
+    for dims, shp in zip(in_dims, in_sizes):
+        if len(set(dims)) != len(dims):
+            raise LayoutError("DUP_DIM", str(dims))
+        for d, n in zip(dims, shp):
+            if sizes.setdefault(d, n) != n:
+                raise EinsumError("SIZE_MISMATCH", d)
+    if len(set(out_dims)) != len(out_dims):
+        raise LayoutError("DUP_DIM", str(out_dims))
+    for d in out_dims:
+        if d not in sizes:
+            raise EinsumError("OUT_NOT_SUBSET", d)
+    union = tuple(sizes)
+    restr = tensor_layout(union, mesh, layout)        # injectivity over the whole einsum
+    origin = (0,) * len(mesh)
+    loc = {}
+    for d in union:
+        _, (n,) = slice_spec((d,), (sizes[d],), mesh, layout, origin)
+        loc[d] = n
+    reduced = tuple(d for d in union if d not in out_dims)
+    reduce_axes = sorted({restr[d] for d in reduced if d in restr})
+    space_g = space_l = 1
+    for d in union:
+        space_g *= sizes[d]
+        space_l *= loc[d]
+    return dict(union=sizes, reduced=reduced, reduce_axes=reduce_axes,
+                local_in=[tuple(loc[d] for d in dims) for dims in in_dims],
+                local_out=tuple(loc[d] for d in out_dims),
+                flops_global=2 * space_g, flops_local=2 * space_l)
+
+
+def all_coords(mesh):
+    return list(itertools.product(*[range(s) for _, s in mesh]))
+
+
+def lowered_einsum(inputs, out_dims, mesh, layout):
+    """Run the einsum the way the mesh would: per-processor local einsum on slices, then
+    the grouped Allreduce.  Returns (local, reduced): dicts coord -> NT, `local` holding
+    every processor's partial result and `reduced` what it holds after the Allreduce."""
+    plan = einsum_plan([t.dims for t in inputs], [t.data.shape for t in inputs],
+                       out_dims, mesh, layout)
+    local = {}
+    for c in all_coords(mesh):
+        local[c] = einsum([slice_tensor(t, mesh, layout, c) for t in inputs], out_dims)
+    reduced = {}
+    axes = plan["reduce_axes"]
+    for c in all_coords(mesh):
+        acc = np.zeros_like(local[c].data)
+        for c2 in all_coords(mesh):            # processors that differ from c only along `axes`
+            if all(c2[i] == c[i] for i in range(len(mesh)) if i not in axes):
+                acc = acc + local[c2].data
+        reduced[c] = NT(acc, tuple(out_dims))
+    return local, reduced
