@@ -1,0 +1,228 @@
+/*
+ * mtf.h — C ABI of the per-processor lowered-einsum path of a mesh-laid-out Transformer layer
+ * (Mesh-TensorFlow, arXiv 1811.02084) for AMD MI355X (gfx950).
+ *
+ * The paper states the problem as: tensors with NAMED dimensions, an n-dimensional MESH of
+ * processors with named dimensions, a global COMPUTATION LAYOUT (partial map tensor-dim ->
+ * mesh-dim) and, for one processor, its COORDINATE in the mesh.  From these follow the slice
+ * of every tensor that processor holds and the local einsum it runs; an einsum whose
+ * reduced-out dimension is split leaves a PARTIAL SUM that an Allreduce over the matching
+ * mesh dimensions completes.  This library computes exactly one processor's share.
+ *
+ * Conventions (all entry points)
+ *   - Return value: MTF_OK (0) or a negative mtf_status.  Nothing throws or aborts across the
+ *     ABI.  On error no output buffer has been written by the failing call (host outputs are
+ *     untouched; no kernel has been launched).  mtf_last_error() gives a thread-local text.
+ *   - Tensors are dense, row-major in the order their dims are listed, 16-byte aligned.
+ *   - "host" pointers are ordinary memory; "device" pointers are HIP device memory owned by
+ *     the caller.  The library never allocates or frees device memory; scratch comes in
+ *     through `workspace` arguments sized by the mtf_*_workspace_bytes() calls.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Device calls
+ *     are asynchronous on it; the library never synchronises.
+ *   - Host-only calls (mtf_slice, mtf_einsum_plan, rank/coord helpers, *_workspace_bytes,
+ *     mtf_status_string) touch no GPU and work on a machine without one.
+ */
+#ifndef MTF_H_
+#define MTF_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define MTF_MAX_RANK 8 /* dims per tensor and per mesh */
+
+/* A named dimension (section "Mesh-TensorFlow: Beyond Batch Splitting": tensor dims and mesh
+ * dims both carry names; the code fragment of the worked example builds them as (name, size)). */
+typedef struct {
+  const char* name; /* host, NUL-terminated, owned by caller */
+  int64_t size;     /* > 0 */
+} mtf_dim;
+
+/* Ordered list of named dims: a tensor shape (row-major, first dim slowest) or a mesh shape. */
+typedef struct {
+  const mtf_dim* dims; /* host */
+  int32_t rank;        /* 0..MTF_MAX_RANK */
+} mtf_shape;
+
+/* One pair of the computation layout: tensor dim `tensor_dim` is split over mesh dim `mesh_dim`. */
+typedef struct {
+  const char* tensor_dim;
+  const char* mesh_dim;
+} mtf_rule;
+
+/* Where the computation runs: mesh shape, global computation layout, this processor's
+ * coordinate (one entry per mesh dim, host array of length mesh.rank). */
+typedef struct {
+  mtf_shape mesh;
+  const mtf_rule* rules; /* host, may be NULL when n_rules == 0 (everything replicated) */
+  int32_t n_rules;
+  const int64_t* coord;  /* host */
+} mtf_place;
+
+typedef enum { MTF_F32 = 0, MTF_BF16 = 1 } mtf_dtype;
+
+/* Component-wise operation fused into the einsum's store (section "Operation Implementation",
+ * component-wise paragraph: same shape and layout in and out, purely local). */
+typedef enum {
+  MTF_EPI_NONE = 0,
+  MTF_EPI_RELU = 1,     /* out = max(value, 0) */
+  MTF_EPI_MASK_GT0 = 2  /* out = aux > 0 ? value : 0; aux has out's shape and the input dtype */
+} mtf_epilogue;
+
+typedef enum {
+  MTF_OK = 0,
+  MTF_ERR_NULL = -1,             /* required pointer is NULL */
+  MTF_ERR_DUP_DIM = -2,          /* two identically named dims in one tensor / mesh / output */
+  MTF_ERR_SIZE_MISMATCH = -3,    /* one name, different sizes across operands; size <= 0 */
+  MTF_ERR_INDIVISIBLE = -4,      /* split dim not divisible by the mesh dim's size */
+  MTF_ERR_LAYOUT_CONFLICT = -5,  /* two dims of one tensor (or of one einsum) on one mesh dim */
+  MTF_ERR_DUP_RULE = -6,         /* a tensor dim appears in two layout rules */
+  MTF_ERR_UNKNOWN_MESH_DIM = -7, /* a rule names a mesh dim the mesh lacks */
+  MTF_ERR_COORD_RANGE = -8,      /* coordinate / rank outside the mesh */
+  MTF_ERR_OUT_NOT_SUBSET = -9,   /* output dim present in no input */
+  MTF_ERR_UNSUPPORTED = -10,     /* legal request this build has no kernel for */
+  MTF_ERR_WORKSPACE = -11,       /* workspace missing or too small */
+  MTF_ERR_HIP = -12,             /* a HIP runtime call failed (text in mtf_last_error) */
+  MTF_ERR_RANK = -13,            /* rank outside 0..MTF_MAX_RANK */
+  MTF_ERR_ALIGN = -14            /* device pointer not 16-byte aligned */
+} mtf_status;
+
+const char* mtf_status_string(int code);
+const char* mtf_last_error(void); /* thread-local; valid until the thread's next failing call */
+
+/* ---------------------------------------------------------------- host: mesh numbering
+ * Processors are numbered row-major over the mesh shape, last mesh dim fastest; this is what
+ * lets one set of processors be viewed as meshes [16,16,2], [32,16] or [512] (section
+ * "Hardware Assumptions").  coord: host array, length mesh->rank. */
+int mtf_rank_to_coord(const mtf_shape* mesh, int64_t rank, int64_t* coord);
+int mtf_coord_to_rank(const mtf_shape* mesh, const int64_t* coord, int64_t* rank);
+
+/* ---------------------------------------------------------------- host: slice of a tensor
+ * Section "Tensor Representations".  The tensor's layout is the restriction of the computation
+ * layout to its dims (rules naming other dims are ignored) and must be injective.  A dim mapped
+ * to mesh dim m of size n_m keeps the contiguous stripe [c*size/n_m, (c+1)*size/n_m) for
+ * coordinate c; other dims are kept whole.  offset/size: host arrays of length t->rank.
+ * Errors: NULL, RANK, DUP_DIM, SIZE_MISMATCH, DUP_RULE, UNKNOWN_MESH_DIM, COORD_RANGE,
+ * LAYOUT_CONFLICT, INDIVISIBLE. */
+int mtf_slice(const mtf_shape* t, const mtf_place* p, int64_t* offset, int64_t* size);
+
+/* ---------------------------------------------------------------- host: lowering of one einsum
+ * Section "Operation Implementation", einsum paragraph: the einsum runs locally on the slices;
+ * the result must then be summed over every mesh dim that a reduced-out, split tensor dim maps
+ * to.  a, b, out are GLOBAL shapes (b may be NULL for a one-operand einsum).  Outputs (any may
+ * be NULL): local sizes of a, b, out (host arrays of the operand's rank); bit m of
+ * *reduce_mesh_dims_mask set iff the partial result needs an Allreduce over mesh dim m;
+ * *flops_local = 2 x local iteration-space size (Appendix B, "Iteration Space").
+ * The union of the operands' dims obeys the same injectivity rule as a single tensor.
+ * Additional errors: OUT_NOT_SUBSET. */
+int mtf_einsum_plan(const mtf_shape* a, const mtf_shape* b, const mtf_shape* out,
+                    const mtf_place* p, int64_t* a_local, int64_t* b_local, int64_t* out_local,
+                    uint32_t* reduce_mesh_dims_mask, int64_t* flops_local);
+
+/* ---------------------------------------------------------------- device: slice gather / scatter
+ * Copies the slice mtf_slice() describes between a full tensor and a contiguous slice buffer
+ * (scatter = 0: slice <- full;  scatter != 0: full <- slice).  full, slice: device.  Bit-exact. */
+int mtf_slice_copy(const void* full, void* slice, const mtf_shape* t, const mtf_place* p,
+                   mtf_dtype dt, int scatter, void* stream);
+
+/* ---------------------------------------------------------------- device: the local einsum
+ * out[out dims] (+)= alpha * sum over dims not in out of a[...] * b[...], then the epilogue.
+ * Shapes are LOCAL (what mtf_einsum_plan returned); names decide everything (einsum paragraph
+ * of "Operation Implementation").  in_dt is the dtype of a, b and aux; accumulation is fp32.
+ * accumulate != 0 adds to the existing out (read in out_dt) before the epilogue.
+ * bf16 operands whose dims fold to a (batched) matrix product run on MFMA; anything else runs
+ * on a generic fp32 FMA kernel.  b may be NULL (one-operand einsum: reductions, transposes).
+ * Errors: NULL, RANK, DUP_DIM, SIZE_MISMATCH, OUT_NOT_SUBSET, ALIGN, UNSUPPORTED, HIP. */
+int mtf_einsum_local(const void* a, const mtf_shape* a_local, const void* b,
+                     const mtf_shape* b_local, void* out, const mtf_shape* out_local,
+                     mtf_dtype in_dt, mtf_dtype out_dt, mtf_epilogue epi, const void* aux,
+                     float alpha, int accumulate, void* stream);
+
+/* ---------------------------------------------------------------- device: partial-sum reduce
+ * out[i] = (residual ? residual[i] : 0) + partials[0][i] + ... + partials[n-1][i], summed in
+ * fp32 in that fixed order.  Stands in, on one GPU, for the Allreduce over one group of a
+ * virtual mesh ("summed up by processor-column" in the 2-D layout of the worked example).
+ * partials: HOST array of n (1..64) DEVICE pointers to fp32 buffers of `count` elements. */
+int mtf_reduce_partials(const void* const* partials, int32_t n, const void* residual,
+                        mtf_dtype residual_dt, void* out, mtf_dtype out_dt, int64_t count,
+                        void* stream);
+
+/* Element-wise dtype conversion (fp32 <-> bf16 round-to-nearest-even, or copy). */
+int mtf_cast(const void* in, mtf_dtype in_dt, void* out, mtf_dtype out_dt, int64_t count,
+             void* stream);
+
+/* ---------------------------------------------------------------- device: fixed layer steps
+ * One processor's share of the two sublayers of the model-parallel Transformer (section
+ * 'Model-Parallel "Transformer"': d_ff and heads are split, so W_in[d_model,d_ff], W_out[d_ff,
+ * d_model], W_{q,k,v}[d_model,heads,d_k], W_o[heads,d_k,d_model] are local slices and y / dx
+ * are partial sums).  All sizes are LOCAL.  Activations and weights are bf16; partial sums and
+ * parameter gradients are fp32.  d_v = d_k. */
+typedef struct {
+  int64_t batch, length, d_model, d_ff;
+} mtf_ffn_dims;
+
+typedef struct {
+  int64_t batch, length, d_model, heads, d_k;
+} mtf_mha_dims;
+
+typedef struct {
+  int64_t batch, length, d_model, heads, d_k, d_ff;
+} mtf_layer_dims;
+
+/* Worked example y = Relu(x w) v without bias.
+ * x[batch,length,d_model], w_in[d_model,d_ff], w_out[d_ff,d_model] (bf16, in);
+ * a[batch,length,d_ff] = relu(x w_in) (bf16, out, saved for backward);
+ * y_partial[batch,length,d_model] (fp32, out). */
+int mtf_ffn_fwd(const mtf_ffn_dims* d, const void* x, const void* w_in, const void* w_out,
+                void* a, void* y_partial, void* stream);
+
+size_t mtf_ffn_bwd_workspace_bytes(const mtf_ffn_dims* d);
+/* dy[batch,length,d_model] bf16 in;  dw_in[d_model,d_ff], dw_out[d_ff,d_model],
+ * dx_partial[batch,length,d_model] fp32 out.  The ReLU mask is a > 0. */
+int mtf_ffn_bwd(const mtf_ffn_dims* d, const void* x, const void* a, const void* w_in,
+                const void* w_out, const void* dy, void* dw_in, void* dw_out, void* dx_partial,
+                void* workspace, size_t workspace_bytes, void* stream);
+
+/* Self-attention over x (memory = x).  logits = scale * q.k over d_k; softmax over the memory
+ * positions; causal != 0 hides memory positions m > l.  Outputs q,k,v,ctx [batch,length,heads,
+ * d_k] bf16 and lse [batch,heads,length] fp32 are saved for backward; y_partial fp32. */
+int mtf_mha_fwd(const mtf_mha_dims* d, const void* x, const void* w_q, const void* w_k,
+                const void* w_v, const void* w_o, float scale, int causal, void* q, void* k,
+                void* v, void* ctx, void* lse, void* y_partial, void* stream);
+
+size_t mtf_mha_bwd_workspace_bytes(const mtf_mha_dims* d);
+int mtf_mha_bwd(const mtf_mha_dims* d, const void* x, const void* w_q, const void* w_k,
+                const void* w_v, const void* w_o, const void* q, const void* k, const void* v,
+                const void* ctx, const void* lse, const void* dy, float scale, int causal,
+                void* dw_q, void* dw_k, void* dw_v, void* dw_o, void* dx_partial,
+                void* workspace, size_t workspace_bytes, void* stream);
+
+/* Whole layer for a one-slice Allreduce group: u = x + MHA(x), z = u + FFN(u); u, z bf16. */
+typedef struct {
+  const void *w_q, *w_k, *w_v, *w_o, *w_in, *w_out; /* device, bf16 */
+} mtf_layer_weights;
+typedef struct {
+  void *q, *k, *v, *ctx, *lse, *u, *a; /* device; lse fp32, others bf16 */
+} mtf_layer_saved;
+typedef struct {
+  void *dw_q, *dw_k, *dw_v, *dw_o, *dw_in, *dw_out; /* device, fp32 */
+} mtf_layer_grads;
+
+size_t mtf_layer_fwd_workspace_bytes(const mtf_layer_dims* d);
+int mtf_layer_fwd(const mtf_layer_dims* d, const void* x, const mtf_layer_weights* w, float scale,
+                  int causal, const mtf_layer_saved* saved, void* z, void* workspace,
+                  size_t workspace_bytes, void* stream);
+
+size_t mtf_layer_bwd_workspace_bytes(const mtf_layer_dims* d);
+int mtf_layer_bwd(const mtf_layer_dims* d, const void* x, const mtf_layer_weights* w,
+                  const mtf_layer_saved* saved, const void* dz, float scale, int causal,
+                  const mtf_layer_grads* g, void* dx, void* workspace, size_t workspace_bytes,
+                  void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MTF_H_ */

@@ -1,0 +1,261 @@
+"""ctypes binding of include/mtf.h — same names, argument marshalling only."""
+import ctypes as C
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmtf.so")
+if not os.path.exists(LIB_PATH):
+    raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_1811_02084_amd.build` "
+                      "(there is no CPU or PyTorch fallback)")
+lib = C.CDLL(LIB_PATH)
+
+MAX_RANK = 8
+F32, BF16 = 0, 1
+EPI_NONE, EPI_RELU, EPI_MASK_GT0 = 0, 1, 2
+
+STATUS = {0: "MTF_OK", -1: "MTF_ERR_NULL", -2: "MTF_ERR_DUP_DIM", -3: "MTF_ERR_SIZE_MISMATCH",
+          -4: "MTF_ERR_INDIVISIBLE", -5: "MTF_ERR_LAYOUT_CONFLICT", -6: "MTF_ERR_DUP_RULE",
+          -7: "MTF_ERR_UNKNOWN_MESH_DIM", -8: "MTF_ERR_COORD_RANGE", -9: "MTF_ERR_OUT_NOT_SUBSET",
+          -10: "MTF_ERR_UNSUPPORTED", -11: "MTF_ERR_WORKSPACE", -12: "MTF_ERR_HIP",
+          -13: "MTF_ERR_RANK", -14: "MTF_ERR_ALIGN"}
+
+
+class mtf_dim(C.Structure):
+    _fields_ = [("name", C.c_char_p), ("size", C.c_int64)]
+
+
+class mtf_shape(C.Structure):
+    _fields_ = [("dims", C.POINTER(mtf_dim)), ("rank", C.c_int32)]
+
+
+class mtf_rule(C.Structure):
+    _fields_ = [("tensor_dim", C.c_char_p), ("mesh_dim", C.c_char_p)]
+
+
+class mtf_place(C.Structure):
+    _fields_ = [("mesh", mtf_shape), ("rules", C.POINTER(mtf_rule)), ("n_rules", C.c_int32),
+                ("coord", C.POINTER(C.c_int64))]
+
+
+class mtf_ffn_dims(C.Structure):
+    _fields_ = [(n, C.c_int64) for n in ("batch", "length", "d_model", "d_ff")]
+
+
+class mtf_mha_dims(C.Structure):
+    _fields_ = [(n, C.c_int64) for n in ("batch", "length", "d_model", "heads", "d_k")]
+
+
+class mtf_layer_dims(C.Structure):
+    _fields_ = [(n, C.c_int64) for n in ("batch", "length", "d_model", "heads", "d_k", "d_ff")]
+
+
+class mtf_layer_weights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("w_q", "w_k", "w_v", "w_o", "w_in", "w_out")]
+
+
+class mtf_layer_saved(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("q", "k", "v", "ctx", "lse", "u", "a")]
+
+
+class mtf_layer_grads(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("dw_q", "dw_k", "dw_v", "dw_o", "dw_in", "dw_out")]
+
+
+class MtfError(RuntimeError):
+    def __init__(self, code):
+        self.code = code
+        self.name = STATUS.get(code, str(code))
+        super().__init__(lib.mtf_last_error().decode() or self.name)
+
+
+lib.mtf_status_string.restype = C.c_char_p
+lib.mtf_last_error.restype = C.c_char_p
+for _f in ("mtf_ffn_bwd_workspace_bytes", "mtf_mha_bwd_workspace_bytes",
+           "mtf_layer_fwd_workspace_bytes", "mtf_layer_bwd_workspace_bytes"):
+    if hasattr(lib, _f):
+        getattr(lib, _f).restype = C.c_size_t
+
+
+def _check(rc):
+    if rc != 0:
+        raise MtfError(rc)
+
+
+def status_string(code):
+    return lib.mtf_status_string(int(code)).decode()
+
+
+# ------------------------------------------------------------------ marshalling helpers
+class _Keep:
+    """Holds the ctypes objects a struct points to for the duration of a call."""
+
+    def __init__(self):
+        self.refs = []
+
+    def shape(self, dims):
+        """dims: sequence of (name, size)."""
+        dims = list(dims)
+        arr = (mtf_dim * max(len(dims), 1))()
+        for i, (n, s) in enumerate(dims):
+            arr[i].name = n.encode() if isinstance(n, str) else n
+            arr[i].size = int(s)
+        self.refs.append(arr)
+        return mtf_shape(C.cast(arr, C.POINTER(mtf_dim)), len(dims))
+
+    def place(self, mesh, layout, coord):
+        layout = list(layout)
+        rules = (mtf_rule * max(len(layout), 1))()
+        for i, (t, m) in enumerate(layout):
+            rules[i].tensor_dim = t.encode()
+            rules[i].mesh_dim = m.encode()
+        self.refs.append(rules)
+        p = mtf_place()
+        p.mesh = self.shape(mesh)
+        p.rules = C.cast(rules, C.POINTER(mtf_rule)) if layout else None
+        p.n_rules = len(layout)
+        if coord is not None:
+            carr = (C.c_int64 * max(len(coord), 1))(*[int(c) for c in coord])
+            self.refs.append(carr)
+            p.coord = C.cast(carr, C.POINTER(C.c_int64))
+        else:
+            p.coord = None
+        return p
+
+
+def _dt(t):
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def _torch_dt(code):
+    return torch.float32 if code == F32 else torch.bfloat16
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("tensors must be contiguous device tensors")
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _named(t, dims):
+    dims = list(dims)
+    if len(dims) != t.dim():
+        raise ValueError(f"{t.dim()}-d tensor given {len(dims)} dim names")
+    return [(n, s) for n, s in zip(dims, t.shape)]
+
+
+# ------------------------------------------------------------------ host-only calls
+def rank_to_coord(mesh, rank):
+    k = _Keep()
+    m = k.shape(mesh)
+    out = (C.c_int64 * max(len(mesh), 1))()
+    _check(lib.mtf_rank_to_coord(C.byref(m), C.c_int64(rank), out))
+    return tuple(out[i] for i in range(len(mesh)))
+
+
+def coord_to_rank(mesh, coord):
+    k = _Keep()
+    m = k.shape(mesh)
+    carr = (C.c_int64 * max(len(mesh), 1))(*[int(c) for c in coord])
+    out = C.c_int64()
+    _check(lib.mtf_coord_to_rank(C.byref(m), carr, C.byref(out)))
+    return out.value
+
+
+def slice(shape, mesh, layout, coord):
+    """shape: [(name, size)...] -> (offsets, sizes) of the slice held at `coord`."""
+    k = _Keep()
+    s = k.shape(shape)
+    p = k.place(mesh, layout, coord)
+    n = max(len(shape), 1)
+    off, sz = (C.c_int64 * n)(), (C.c_int64 * n)()
+    _check(lib.mtf_slice(C.byref(s), C.byref(p), off, sz))
+    return tuple(off[i] for i in range(len(shape))), tuple(sz[i] for i in range(len(shape)))
+
+
+def einsum_plan(a, b, out, mesh, layout):
+    """a, b, out: global shapes [(name, size)...] (b may be None).  Returns dict with local
+    sizes, reduce_axes (mesh dim indices needing an Allreduce) and flops_local."""
+    k = _Keep()
+    sa, so = k.shape(a), k.shape(out)
+    sb = k.shape(b) if b is not None else None
+    p = k.place(mesh, layout, None)
+    la = (C.c_int64 * max(len(a), 1))()
+    lb = (C.c_int64 * max(len(b) if b is not None else 0, 1))()
+    lo = (C.c_int64 * max(len(out), 1))()
+    mask, fl = C.c_uint32(), C.c_int64()
+    _check(lib.mtf_einsum_plan(C.byref(sa), C.byref(sb) if sb is not None else None, C.byref(so),
+                               C.byref(p), la, lb, lo, C.byref(mask), C.byref(fl)))
+    return dict(local_in=[tuple(la[i] for i in range(len(a)))] +
+                ([tuple(lb[i] for i in range(len(b)))] if b is not None else []),
+                local_out=tuple(lo[i] for i in range(len(out))),
+                reduce_axes=[i for i in range(len(mesh)) if mask.value >> i & 1],
+                flops_local=fl.value)
+
+
+# ------------------------------------------------------------------ device calls
+def slice_copy(full, dims, mesh, layout, coord, slice_buf=None, scatter=False):
+    """Gathers the slice of `full` (scatter=False) or writes slice_buf back into it."""
+    k = _Keep()
+    shp = _named(full, dims)
+    s = k.shape(shp)
+    p = k.place(mesh, layout, coord)
+    if slice_buf is None:
+        _, sz = slice(shp, mesh, layout, coord)
+        slice_buf = torch.empty(sz, dtype=full.dtype, device=full.device)
+    _check(lib.mtf_slice_copy(_ptr(full), _ptr(slice_buf), C.byref(s), C.byref(p), _dt(full),
+                              1 if scatter else 0, _stream()))
+    return slice_buf
+
+
+def einsum_local(a, a_dims, b, b_dims, out_dims, out_dtype=None, epi=EPI_NONE, aux=None,
+                 alpha=1.0, accumulate=False, out=None):
+    k = _Keep()
+    sa = k.shape(_named(a, a_dims))
+    sb = k.shape(_named(b, b_dims)) if b is not None else None
+    sizes = dict(_named(a, a_dims))
+    if b is not None:
+        sizes.update(_named(b, b_dims))
+    missing = [d for d in out_dims if d not in sizes]
+    out_shape = [(d, sizes.get(d, 1)) for d in out_dims]
+    if out is None:
+        if missing:      # let the library report it; no buffer is needed for that
+            out = torch.empty(1, dtype=out_dtype or a.dtype, device=a.device)
+        else:
+            out = torch.empty([s for _, s in out_shape], dtype=out_dtype or a.dtype, device=a.device)
+    so = k.shape(out_shape)
+    _check(lib.mtf_einsum_local(_ptr(a), C.byref(sa), _ptr(b), C.byref(sb) if sb is not None else None,
+                                _ptr(out), C.byref(so), _dt(a), _dt(out), int(epi), _ptr(aux),
+                                C.c_float(alpha), 1 if accumulate else 0, _stream()))
+    return out
+
+
+def reduce_partials(partials, residual=None, out_dtype=torch.float32, out=None):
+    n = len(partials)
+    count = partials[0].numel()
+    arr = (C.c_void_p * n)(*[p.data_ptr() for p in partials])
+    for p in partials:
+        if p.dtype != torch.float32 or p.numel() != count or not p.is_contiguous():
+            raise ValueError("partials must be contiguous fp32 tensors of one size")
+    if out is None:
+        out = torch.empty(partials[0].shape, dtype=out_dtype, device=partials[0].device)
+    _check(lib.mtf_reduce_partials(arr, n, _ptr(residual), _dt(residual) if residual is not None else F32,
+                                   _ptr(out), _dt(out), C.c_int64(count), _stream()))
+    return out
+
+
+def cast(x, dtype):
+    out = torch.empty(x.shape, dtype=dtype, device=x.device)
+    _check(lib.mtf_cast(_ptr(x), _dt(x), _ptr(out), _dt(out), C.c_int64(x.numel()), _stream()))
+    return out

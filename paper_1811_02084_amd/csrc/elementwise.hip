@@ -1,0 +1,219 @@
+// HBM-bound helpers: slice gather/scatter, partial-sum reduce, dtype cast.
+#include "device_common.h"
+
+namespace mtf {
+
+// ------------------------------------------------------------------------------ slice copy
+// The slice is a dense box inside a dense row-major tensor ("Tensor Representations": every
+// split dim keeps one contiguous stripe).  After merging dims the box has <= MTF_MAX_RANK dims;
+// the innermost is copied in vectors of VEC elements.
+struct BoxArgs {
+  int rank;
+  int64_t extent[MTF_MAX_RANK];  // box extents, innermost counted in vectors
+  int64_t stride[MTF_MAX_RANK];  // element strides of the full tensor
+  int64_t base;                  // element offset of the box origin in the full tensor
+  int64_t vectors;               // total vectors in the box
+};
+
+template <typename VecT, int VEC_ELEMS, typename ElemT>
+__global__ void __launch_bounds__(256) slice_copy_kernel(const ElemT* __restrict__ full_c,
+                                                        ElemT* __restrict__ full_m,
+                                                        ElemT* __restrict__ slice, BoxArgs box,
+                                                        int scatter) {
+  for (int64_t v = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; v < box.vectors;
+       v += (int64_t)gridDim.x * blockDim.x) {
+    int64_t rem = v, off = box.base;
+    for (int d = box.rank - 1; d >= 0; --d) {
+      int64_t i = rem % box.extent[d];
+      rem /= box.extent[d];
+      off += i * box.stride[d] * (d == box.rank - 1 ? VEC_ELEMS : 1);
+    }
+    VecT* s = reinterpret_cast<VecT*>(slice + v * VEC_ELEMS);
+    if (scatter)
+      *reinterpret_cast<VecT*>(full_m + off) = *s;
+    else
+      *s = *reinterpret_cast<const VecT*>(full_c + off);
+  }
+}
+
+template <typename ElemT>
+static int slice_copy_typed(const void* full, void* slice, const Dims& t, const int64_t* offset,
+                            const int64_t* size, int scatter, hipStream_t stream) {
+  // full-tensor strides
+  int64_t stride[MTF_MAX_RANK], acc = 1;
+  for (int i = t.rank - 1; i >= 0; --i) {
+    stride[i] = acc;
+    acc *= t.size[i];
+  }
+  BoxArgs box;
+  box.rank = 0;
+  box.base = 0;
+  int64_t elems = 1;
+  for (int i = 0; i < t.rank; ++i) {
+    box.base += offset[i] * stride[i];
+    elems *= size[i];
+    // merge with the previous box dim when that keeps addressing linear: the current dim must be
+    // whole (not split) for its outer neighbour's stride to continue it
+    if (box.rank > 0 && size[i] == t.size[i]) {
+      box.extent[box.rank - 1] *= size[i];
+      box.stride[box.rank - 1] = stride[i];
+    } else {
+      box.extent[box.rank] = size[i];
+      box.stride[box.rank] = stride[i];
+      ++box.rank;
+    }
+  }
+  if (box.rank == 0) {  // rank-0 tensor: one element
+    box.rank = 1;
+    box.extent[0] = 1;
+    box.stride[0] = 1;
+  }
+  if (elems == 0) return MTF_OK;
+  const int kVec = 16 / (int)sizeof(ElemT);
+  int64_t inner = box.extent[box.rank - 1];
+  bool vec_ok = inner % kVec == 0 && box.base % kVec == 0 && aligned16(full) && aligned16(slice);
+  for (int d = 0; d + 1 < box.rank; ++d) vec_ok = vec_ok && box.stride[d] % kVec == 0;
+  const ElemT* fc = static_cast<const ElemT*>(full);
+  ElemT* fm = scatter ? const_cast<ElemT*>(fc) : nullptr;
+  if (vec_ok) {
+    box.extent[box.rank - 1] = inner / kVec;
+    box.vectors = elems / kVec;
+    int blocks = (int)std::min<int64_t>(ceil_div(box.vectors, 256), 256 * 16);
+    slice_copy_kernel<uint4, kVec, ElemT><<<blocks, 256, 0, stream>>>(fc, fm, static_cast<ElemT*>(slice), box, scatter);
+  } else {
+    box.vectors = elems;
+    int blocks = (int)std::min<int64_t>(ceil_div(box.vectors, 256), 256 * 16);
+    slice_copy_kernel<ElemT, 1, ElemT><<<blocks, 256, 0, stream>>>(fc, fm, static_cast<ElemT*>(slice), box, scatter);
+  }
+  return launch_status("slice_copy_kernel");
+}
+
+// ------------------------------------------------------------------------------ partial-sum reduce
+struct PartialPtrs {
+  const float* p[64];
+};
+
+template <bool RES_BF16, bool OUT_BF16>
+__global__ void __launch_bounds__(256) reduce_partials_kernel(PartialPtrs parts, int n,
+                                                             const void* __restrict__ residual,
+                                                             void* __restrict__ out, int64_t count) {
+  const int64_t vecs = count / 4;
+  for (int64_t v = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; v < vecs;
+       v += (int64_t)gridDim.x * blockDim.x) {
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (residual) {
+      if (RES_BF16) {
+        uint2 r = reinterpret_cast<const uint2*>(residual)[v];
+        acc = make_float4(__uint_as_float(r.x << 16), __uint_as_float(r.x & 0xffff0000u),
+                          __uint_as_float(r.y << 16), __uint_as_float(r.y & 0xffff0000u));
+      } else {
+        acc = reinterpret_cast<const float4*>(residual)[v];
+      }
+    }
+    for (int i = 0; i < n; ++i) {  // fixed order: residual, then partial 0, 1, ...
+      float4 x = reinterpret_cast<const float4*>(parts.p[i])[v];
+      acc.x += x.x;
+      acc.y += x.y;
+      acc.z += x.z;
+      acc.w += x.w;
+    }
+    if (OUT_BF16)
+      reinterpret_cast<uint2*>(out)[v] = make_uint2(pack_bf16x2(acc.x, acc.y), pack_bf16x2(acc.z, acc.w));
+    else
+      reinterpret_cast<float4*>(out)[v] = acc;
+  }
+  // ragged tail (count not a multiple of 4): one thread each
+  int64_t t = vecs * 4 + blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+  if (t < count) {
+    float acc = 0.f;
+    if (residual)
+      acc = RES_BF16 ? bf16_to_f32(static_cast<const bf16_t*>(residual)[t])
+                     : static_cast<const float*>(residual)[t];
+    for (int i = 0; i < n; ++i) acc += parts.p[i][t];
+    if (OUT_BF16)
+      static_cast<bf16_t*>(out)[t] = f32_to_bf16(acc);
+    else
+      static_cast<float*>(out)[t] = acc;
+  }
+}
+
+template <bool IN_BF16, bool OUT_BF16>
+__global__ void __launch_bounds__(256) cast_kernel(const void* __restrict__ in, void* __restrict__ out,
+                                                  int64_t count) {
+  for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < count;
+       i += (int64_t)gridDim.x * blockDim.x) {
+    float v = IN_BF16 ? bf16_to_f32(static_cast<const bf16_t*>(in)[i]) : static_cast<const float*>(in)[i];
+    if (OUT_BF16)
+      static_cast<bf16_t*>(out)[i] = f32_to_bf16(v);
+    else
+      static_cast<float*>(out)[i] = v;
+  }
+}
+
+}  // namespace mtf
+
+using namespace mtf;
+
+extern "C" {
+
+int mtf_slice_copy(const void* full, void* slice, const mtf_shape* t, const mtf_place* p,
+                   mtf_dtype dt, int scatter, void* stream) {
+  Dims d;
+  if (int rc = load_shape(t, "tensor", &d)) return rc;
+  if (!full || !slice) return fail(MTF_ERR_NULL, "full / slice");
+  if (dt != MTF_F32 && dt != MTF_BF16) return fail(MTF_ERR_UNSUPPORTED, "dtype %d", (int)dt);
+  int64_t off[MTF_MAX_RANK], sz[MTF_MAX_RANK];
+  if (int rc = slice_of(d, p, off, sz)) return rc;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  return dt == MTF_F32 ? slice_copy_typed<float>(full, slice, d, off, sz, scatter, s)
+                       : slice_copy_typed<bf16_t>(full, slice, d, off, sz, scatter, s);
+}
+
+int mtf_reduce_partials(const void* const* partials, int32_t n, const void* residual,
+                        mtf_dtype residual_dt, void* out, mtf_dtype out_dt, int64_t count,
+                        void* stream) {
+  if (!partials || !out) return fail(MTF_ERR_NULL, "partials / out");
+  if (n < 1 || n > 64) return fail(MTF_ERR_UNSUPPORTED, "%d partials (1..64)", n);
+  if (count < 0) return fail(MTF_ERR_SIZE_MISMATCH, "count %lld", (long long)count);
+  PartialPtrs pp;
+  for (int i = 0; i < n; ++i) {
+    if (!partials[i]) return fail(MTF_ERR_NULL, "partial %d", i);
+    if (!aligned16(partials[i])) return fail(MTF_ERR_ALIGN, "partial %d", i);
+    pp.p[i] = static_cast<const float*>(partials[i]);
+  }
+  if (!aligned16(out) || !aligned16(residual)) return fail(MTF_ERR_ALIGN, "out / residual");
+  if (count == 0) return MTF_OK;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  int blocks = (int)std::min<int64_t>(ceil_div(ceil_div(count, 4), 256), 256 * 8);
+  bool rb = residual && residual_dt == MTF_BF16, ob = out_dt == MTF_BF16;
+  if (rb && ob)
+    reduce_partials_kernel<true, true><<<blocks, 256, 0, s>>>(pp, n, residual, out, count);
+  else if (rb)
+    reduce_partials_kernel<true, false><<<blocks, 256, 0, s>>>(pp, n, residual, out, count);
+  else if (ob)
+    reduce_partials_kernel<false, true><<<blocks, 256, 0, s>>>(pp, n, residual, out, count);
+  else
+    reduce_partials_kernel<false, false><<<blocks, 256, 0, s>>>(pp, n, residual, out, count);
+  return launch_status("reduce_partials_kernel");
+}
+
+int mtf_cast(const void* in, mtf_dtype in_dt, void* out, mtf_dtype out_dt, int64_t count,
+             void* stream) {
+  if (!in || !out) return fail(MTF_ERR_NULL, "in / out");
+  if (count < 0) return fail(MTF_ERR_SIZE_MISMATCH, "count %lld", (long long)count);
+  if (count == 0) return MTF_OK;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  int blocks = (int)std::min<int64_t>(ceil_div(count, 256), 256 * 8);
+  bool ib = in_dt == MTF_BF16, ob = out_dt == MTF_BF16;
+  if (ib && ob)
+    cast_kernel<true, true><<<blocks, 256, 0, s>>>(in, out, count);
+  else if (ib)
+    cast_kernel<true, false><<<blocks, 256, 0, s>>>(in, out, count);
+  else if (ob)
+    cast_kernel<false, true><<<blocks, 256, 0, s>>>(in, out, count);
+  else
+    cast_kernel<false, false><<<blocks, 256, 0, s>>>(in, out, count);
+  return launch_status("cast_kernel");
+}
+
+}  // extern "C"

@@ -1,0 +1,44 @@
+// Launcher interface of the bf16 MFMA GEMM family (gfx950).
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include "device_common.h"
+
+namespace mtf {
+
+constexpr int kMaxSegments = 3;
+
+// C[z][m][n] (+)= alpha * sum_s sum_k A_s[z][m][k] * B_s[z][k][n], then the epilogue.
+//
+// Operands are bf16.  An operand is either "k-contiguous" (consecutive k adjacent in memory;
+// ld = stride between consecutive m resp. n) or "mn-contiguous" (consecutive m resp. n adjacent;
+// ld = stride between consecutive k).  C is row-major with n contiguous.  Up to kMaxSegments
+// (A, B, K) triples share M, N, the leading dims and the layout flags and are accumulated into
+// one C (a contraction whose reduced dim is spread over several tensors).
+struct GemmDesc {
+  int nseg = 1;
+  const bf16_t* A[kMaxSegments] = {nullptr, nullptr, nullptr};
+  const bf16_t* B[kMaxSegments] = {nullptr, nullptr, nullptr};
+  int64_t K[kMaxSegments] = {0, 0, 0};
+  int64_t M = 0, N = 0;
+  bool a_kcontig = true, b_kcontig = false;
+  int64_t lda = 0, ldb = 0, ldc = 0;
+  void* C = nullptr;
+  bool out_bf16 = false;
+  int epi = MTF_EPI_NONE;      // mtf_epilogue
+  const bf16_t* aux = nullptr; // MTF_EPI_MASK_GT0: same shape / ldc / batch strides as C
+  float alpha = 1.f;
+  bool accumulate = false;
+  // batch: z = z0 * batch1 + z1
+  int64_t batch0 = 1, batch1 = 1;
+  int64_t sA0 = 0, sA1 = 0, sB0 = 0, sB1 = 0, sC0 = 0, sC1 = 0;
+};
+
+// True when the MFMA kernel can run this problem (alignment and divisibility of the leading
+// dims by 8 elements); otherwise the caller must use the generic kernel.
+bool gemm_bf16_supported(const GemmDesc& d);
+
+// Enqueues the GEMM on `stream`.  Returns MTF_OK or an error code (nothing launched on error).
+int gemm_bf16_launch(const GemmDesc& d, hipStream_t stream);
+
+}  // namespace mtf

@@ -1,0 +1,374 @@
+// bf16 x bf16 -> fp32-accumulate GEMM on the gfx950 matrix cores, with fused component-wise
+// epilogues.  Every contraction of the Transformer-layer path lowers to this kernel (the paper's
+// "computation time is dominated by that of einsum operations").
+//
+// Design (MI355X):
+//   * one workgroup = 8 wavefronts (2 per SIMD) computes a 256x256 tile of C, K advanced 64 at
+//     a time; each wave owns 128x64 of it as 4x2 accumulators of v_mfma_f32_32x32x16_bf16;
+//   * operand tiles go global -> LDS directly (global_load_lds_dwordx4, 16 B per lane, no VGPR
+//     staging), double-buffered: 2 stages x (32 KiB A + 32 KiB B) = 128 of the CU's 160 KiB;
+//   * because those loads place lane i's 16 B at slot i of a 1 KiB run, bank-conflict avoidance
+//     is done by permuting WHICH 16-byte chunk each lane fetches (XOR swizzle), not by padding;
+//   * a k-contiguous operand is read back with ds_read_b128 (8 consecutive k for one row);
+//     an m/n-contiguous operand is read with ds_read_b64_tr_b16, the LDS transpose load, so no
+//     operand is ever transposed in memory or registers;
+//   * the MFMA is issued with its operands exchanged (B-fragment as the instruction's A), which
+//     leaves every lane holding 4 consecutive n of one row m: 16-byte fp32 / 8-byte bf16 stores;
+//   * out-of-range chunks (ragged M, N, K) are fetched from a 16-byte block of zeros instead;
+//   * workgroup ids are dealt round-robin to the 8 XCDs by hardware, so ids are remapped to make
+//     each XCD (own L2) work on a compact patch of C.
+#include "gemm_bf16.h"
+
+namespace mtf {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(4 * sizeof(short)))) short s16x4;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
+
+#define LDS_PTR(T, p) ((__attribute__((address_space(3))) T*)(p))
+
+namespace {
+
+constexpr int BM = 256, BN = 256, BK = 64;
+constexpr int kThreads = 512;
+constexpr int kATile = BM * BK * 2;         // bytes
+constexpr int kStage = (BM + BN) * BK * 2;  // bytes
+constexpr int kGroupM = 4;                  // tile rows per L2 patch
+
+__device__ __attribute__((aligned(16))) uint32_t g_zero_chunk[4] = {0u, 0u, 0u, 0u};
+
+struct GemmArgs {
+  const bf16_t* A[kMaxSegments];
+  const bf16_t* B[kMaxSegments];
+  int K[kMaxSegments];
+  int nseg;
+  int M, N;
+  int64_t lda, ldb, ldc;
+  void* C;
+  const bf16_t* aux;
+  float alpha;
+  int accumulate;
+  int tiles_m, tiles_n;
+  int batch1;
+  int64_t sA0, sA1, sB0, sB1, sC0, sC1;
+};
+
+// Direct global -> LDS load of 16 bytes per lane: lane i's bytes land at lds_addr + 16*i.
+// Written as inline assembly on purpose: through the compiler's builtin, every later LDS read
+// is made to wait for ALL outstanding loads of this kind (it cannot tell the two stages apart
+// once more than a handful of such loads exist), which would serialise load and compute.  Here
+// the waits are placed by hand (tile_ready below).  m0 carries the LDS address; nothing else in
+// these kernels uses m0.
+__device__ __forceinline__ void load16_to_lds(const char* uniform_base, uint32_t lane_offset,
+                                              uint32_t lds_addr_uniform) {
+  asm volatile(
+      "s_mov_b32 m0, %0\n\t"
+      "s_nop 0\n\t"
+      "global_load_lds_dwordx4 %1, %2\n"
+      :
+      : "s"(lds_addr_uniform), "v"(lane_offset), "s"(uniform_base)
+      : "memory", "m0");
+}
+
+__device__ __forceinline__ uint32_t lds_address(const char* p) {
+  return (uint32_t)(uintptr_t)LDS_PTR(const char, p);
+}
+
+// One operand tile (256 rows of the M/N index x 64 of k) global -> LDS: 4 loads per lane.
+//   k-contiguous: LDS row = one m (or n), 128 B = 8 chunks; chunk c of row r sits at c ^ ((r>>1)&7)
+//   mn-contiguous: LDS row = one k, 512 B = 32 chunks; chunk c of row k sits at c ^ ((k&3)<<2)
+// TileLoader keeps, per lane, the four loop-invariant byte offsets of its chunks relative to the
+// tile's first element (rows / columns beyond the matrix edge are clamped to the last valid one:
+// they only feed C elements that are never stored); the tile origin itself is wave-uniform.
+template <bool KCONTIG>
+struct TileLoader {
+  uint32_t off[4];  // byte offset of this lane's chunk i from the tile origin (k0 = 0)
+  int kpos[4];      // k of the chunk (k-contiguous) or k-row (mn-contiguous), relative to k0
+
+  __device__ __forceinline__ void init(int64_t ld, int mn0, int mn_limit, int wave, int lane) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int run = i * 8 + wave;
+      if (KCONTIG) {
+        const int r = run * 8 + (lane >> 3);
+        const int c = (lane & 7) ^ ((r >> 1) & 7);
+        const int mn = min(mn0 + r, mn_limit - 1) - mn0;
+        off[i] = (uint32_t)((int64_t)mn * ld * 2 + c * 16);
+        kpos[i] = c * 8;
+      } else {
+        const int kr = run * 2 + (lane >> 5);
+        const int c = (lane & 31) ^ ((kr & 3) << 2);
+        const int mn = min(mn0 + c * 8, mn_limit - 8) - mn0;
+        off[i] = (uint32_t)((int64_t)kr * ld * 2 + mn * 2);
+        kpos[i] = kr;
+      }
+    }
+  }
+
+  // origin: address of element (mn0, k0) of the operand (wave-uniform).
+  __device__ __forceinline__ void issue(const char* origin, char* tile, int wave, int lane,
+                                        int k_left) const {
+    if (k_left >= BK) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) load16_to_lds(origin, off[i], lds_address(tile) + (i * 8 + wave) * 1024);
+    } else {  // ragged last k-tile: chunks past K become zeros
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        char* run = tile + (i * 8 + wave) * 1024;
+        if (kpos[i] < k_left)
+          load16_to_lds(origin, off[i], lds_address(run));
+        else
+          *LDS_PTR(u32x4, run + lane * 16) = u32x4{0u, 0u, 0u, 0u};
+      }
+    }
+  }
+};
+
+// MFMA operand fragment for 32 consecutive m (or n) starting at mn_base and the 16 k of step ks:
+// lane l gets index mn_base + l%32 and k = ks*16 + (l/32)*8 + 0..7.
+template <bool KCONTIG>
+__device__ __forceinline__ bf16x8 read_fragment(const char* tile, int mn_base, int ks, int lane) {
+  if (KCONTIG) {
+    const int r = mn_base + (lane & 31);
+    const int c = ks * 2 + (lane >> 5);
+    return *LDS_PTR(const bf16x8, tile + r * 128 + ((c ^ ((r >> 1) & 7)) << 4));
+  } else {
+    // Transpose load: in each group of 16 lanes, lane j points at 4 consecutive n of k-row j/4;
+    // the hardware hands lane i the 4 k-values of column i.
+    const int g = lane >> 4, j = lane & 15;
+    const int n = mn_base + (g & 1) * 16 + (j & 3) * 4;
+    const int krow = ks * 16 + (g >> 1) * 8 + (j >> 2);
+    const int chunk = (n >> 3) ^ ((j >> 2) << 2);  // (krow & 3) == j >> 2
+    const char* p = tile + krow * 512 + (chunk << 4) + (n & 7) * 2;
+    union {
+      s16x4 h[2];
+      bf16x8 v;
+    } u;
+    u.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, p));
+    u.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, p + 4 * 512));
+    return u.v;
+  }
+}
+
+template <bool A_K, bool B_K, int EPI, bool OUT_BF16>
+__global__ void __launch_bounds__(kThreads) gemm_bf16_kernel(GemmArgs g) {
+  // Two stages, used alternately by the twice-unrolled k loop below.
+  __shared__ __attribute__((aligned(1024))) char stage0[kStage];
+  __shared__ __attribute__((aligned(1024))) char stage1[kStage];
+
+  // ---- which tile: XCD-aware remap, then patches of kGroupM tile rows
+  const int per_xcd = gridDim.x >> 3;
+  const int t = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+  if (t >= g.tiles_m * g.tiles_n) return;
+  const int per_group = kGroupM * g.tiles_n;
+  const int first_m = (t / per_group) * kGroupM;
+  const int rows = min(g.tiles_m - first_m, kGroupM);
+  const int tile_m = first_m + (t % per_group) % rows;
+  const int tile_n = (t % per_group) / rows;
+  const int m0 = tile_m * BM, n0 = tile_n * BN;
+
+  const int z0 = blockIdx.y / g.batch1, z1 = blockIdx.y % g.batch1;
+  const int64_t offA = z0 * g.sA0 + z1 * g.sA1, offB = z0 * g.sB0 + z1 * g.sB1,
+                offC = z0 * g.sC0 + z1 * g.sC1;
+
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int wm = wave >> 2, wn = wave & 3;  // 2 x 4 waves, each 128 (m) x 64 (n)
+
+  f32x16 acc[4][2];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+  // k-tiles of all segments, in order
+  int tiles_in_seg[kMaxSegments];
+  int total_tiles = 0;
+#pragma unroll
+  for (int s = 0; s < kMaxSegments; ++s) {
+    tiles_in_seg[s] = s < g.nseg ? (g.K[s] + BK - 1) / BK : 0;
+    total_tiles += tiles_in_seg[s];
+  }
+
+  TileLoader<A_K> load_a;
+  TileLoader<B_K> load_b;
+  load_a.init(g.lda, m0, g.M, wave, lane);
+  load_b.init(g.ldb, n0, g.N, wave, lane);
+  const int64_t a_tile0 = A_K ? (int64_t)m0 * g.lda : m0, a_kstep = A_K ? 1 : g.lda;
+  const int64_t b_tile0 = B_K ? (int64_t)n0 * g.ldb : n0, b_kstep = B_K ? 1 : g.ldb;
+
+  auto issue = [&](int kt, char* st) {
+    int s = 0, local = kt;
+#pragma unroll
+    for (int q = 0; q < kMaxSegments - 1; ++q)
+      if (s == q && local >= tiles_in_seg[q]) {
+        local -= tiles_in_seg[q];
+        s = q + 1;
+      }
+    const int k0 = local * BK;
+    const bf16_t* pa = g.A[s] + offA + a_tile0 + k0 * a_kstep;
+    const bf16_t* pb = g.B[s] + offB + b_tile0 + k0 * b_kstep;
+    load_a.issue(reinterpret_cast<const char*>(pa), st, wave, lane, g.K[s] - k0);
+    load_b.issue(reinterpret_cast<const char*>(pb), st + kATile, wave, lane, g.K[s] - k0);
+  };
+  auto compute = [&](const char* st) {
+#pragma unroll
+    for (int ks = 0; ks < BK / 16; ++ks) {
+      bf16x8 af[4], bf[2];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) af[i] = read_fragment<A_K>(st, wm * 128 + i * 32, ks, lane);
+#pragma unroll
+      for (int j = 0; j < 2; ++j) bf[j] = read_fragment<B_K>(st + kATile, wn * 64 + j * 32, ks, lane);
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[j], af[i], acc[i][j], 0, 0, 0);
+    }
+  };
+  // Wait for this wave's loads of the tile about to be used, then for everybody's; passing the
+  // barrier also means nobody still reads the other stage, which the next issue() overwrites.
+  auto tile_ready = [&]() {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+  };
+
+  if (total_tiles > 0) issue(0, stage0);
+  for (int kt = 0; kt < total_tiles; kt += 2) {
+    tile_ready();
+    if (kt + 1 < total_tiles) issue(kt + 1, stage1);
+    compute(stage0);
+    if (kt + 1 >= total_tiles) break;
+    tile_ready();
+    if (kt + 2 < total_tiles) issue(kt + 2, stage0);
+    compute(stage1);
+  }
+
+  // ---- epilogue: lane holds row m = .. + lane%32 and, per group q, 4 consecutive n
+  const int lane_m = lane & 31, lane_h = lane >> 5;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int m = m0 + wm * 128 + i * 32 + lane_m;
+    if (m >= g.M) continue;
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int n = n0 + wn * 64 + j * 32 + q * 8 + lane_h * 4;
+        if (n >= g.N) continue;
+        const int64_t idx = offC + (int64_t)m * g.ldc + n;
+        float v[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = g.alpha * acc[i][j][q * 4 + e];
+        if (g.accumulate) {
+          if (OUT_BF16) {
+            uint2 old = *reinterpret_cast<const uint2*>(static_cast<const bf16_t*>(g.C) + idx);
+            v[0] += __uint_as_float(old.x << 16);
+            v[1] += __uint_as_float(old.x & 0xffff0000u);
+            v[2] += __uint_as_float(old.y << 16);
+            v[3] += __uint_as_float(old.y & 0xffff0000u);
+          } else {
+            float4 old = *reinterpret_cast<const float4*>(static_cast<const float*>(g.C) + idx);
+            v[0] += old.x;
+            v[1] += old.y;
+            v[2] += old.z;
+            v[3] += old.w;
+          }
+        }
+        if (EPI == MTF_EPI_RELU) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) v[e] = fmaxf(v[e], 0.f);
+        } else if (EPI == MTF_EPI_MASK_GT0) {
+          uint2 a = *reinterpret_cast<const uint2*>(g.aux + idx);
+          // bf16 > 0  <=>  sign bit clear and magnitude non-zero (NaN counts as not > 0 is not
+          // needed here: the activations are finite)
+          const uint32_t w[4] = {a.x & 0xffffu, a.x >> 16, a.y & 0xffffu, a.y >> 16};
+#pragma unroll
+          for (int e = 0; e < 4; ++e) v[e] = (w[e] != 0u && w[e] < 0x8000u) ? v[e] : 0.f;
+        }
+        if (OUT_BF16)
+          *reinterpret_cast<uint2*>(static_cast<bf16_t*>(g.C) + idx) =
+              make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
+        else
+          *reinterpret_cast<float4*>(static_cast<float*>(g.C) + idx) = make_float4(v[0], v[1], v[2], v[3]);
+      }
+    }
+  }
+}
+
+template <bool A_K, bool B_K, int EPI, bool OUT_BF16>
+int launch_instance(const GemmArgs& a, dim3 grid, hipStream_t stream) {
+  auto kernel = gemm_bf16_kernel<A_K, B_K, EPI, OUT_BF16>;
+  kernel<<<grid, kThreads, 0, stream>>>(a);
+  return launch_status("gemm_bf16_kernel");
+}
+
+template <bool A_K, bool B_K>
+int launch_layout(const GemmDesc& d, const GemmArgs& a, dim3 grid, hipStream_t s) {
+  if (d.out_bf16) {
+    switch (d.epi) {
+      case MTF_EPI_NONE: return launch_instance<A_K, B_K, MTF_EPI_NONE, true>(a, grid, s);
+      case MTF_EPI_RELU: return launch_instance<A_K, B_K, MTF_EPI_RELU, true>(a, grid, s);
+      default: return launch_instance<A_K, B_K, MTF_EPI_MASK_GT0, true>(a, grid, s);
+    }
+  }
+  switch (d.epi) {
+    case MTF_EPI_NONE: return launch_instance<A_K, B_K, MTF_EPI_NONE, false>(a, grid, s);
+    case MTF_EPI_RELU: return launch_instance<A_K, B_K, MTF_EPI_RELU, false>(a, grid, s);
+    default: return launch_instance<A_K, B_K, MTF_EPI_MASK_GT0, false>(a, grid, s);
+  }
+}
+
+}  // namespace
+
+bool gemm_bf16_supported(const GemmDesc& d) {
+  if (d.nseg < 1 || d.nseg > kMaxSegments) return false;
+  if (d.M <= 0 || d.N <= 0 || d.M > INT32_MAX || d.N > INT32_MAX) return false;
+  if (d.lda % 8 || d.ldb % 8 || d.ldc % 4 || d.N % 8) return false;
+  if (!d.a_kcontig && d.M % 8) return false;
+  if (d.sA0 % 8 || d.sA1 % 8 || d.sB0 % 8 || d.sB1 % 8 || d.sC0 % 4 || d.sC1 % 4) return false;
+  for (int s = 0; s < d.nseg; ++s) {
+    if (d.K[s] < 0 || d.K[s] > INT32_MAX) return false;
+    if ((d.a_kcontig || d.b_kcontig) && d.K[s] % 8) return false;
+    if (!aligned16(d.A[s]) || !aligned16(d.B[s])) return false;
+  }
+  if (!aligned16(d.C) || (d.epi == MTF_EPI_MASK_GT0 && (!d.aux || !aligned16(d.aux)))) return false;
+  if (d.batch0 * d.batch1 > 65535) return false;
+  return true;
+}
+
+int gemm_bf16_launch(const GemmDesc& d, hipStream_t stream) {
+  if (!gemm_bf16_supported(d)) return fail(MTF_ERR_UNSUPPORTED, "GEMM shape/alignment");
+  GemmArgs a;
+  for (int s = 0; s < kMaxSegments; ++s) {
+    a.A[s] = s < d.nseg ? d.A[s] : d.A[0];
+    a.B[s] = s < d.nseg ? d.B[s] : d.B[0];
+    a.K[s] = s < d.nseg ? (int)d.K[s] : 0;
+  }
+  a.nseg = d.nseg;
+  a.M = (int)d.M;
+  a.N = (int)d.N;
+  a.lda = d.lda;
+  a.ldb = d.ldb;
+  a.ldc = d.ldc;
+  a.C = d.C;
+  a.aux = d.aux;
+  a.alpha = d.alpha;
+  a.accumulate = d.accumulate ? 1 : 0;
+  a.tiles_m = (int)ceil_div(d.M, BM);
+  a.tiles_n = (int)ceil_div(d.N, BN);
+  a.batch1 = (int)d.batch1;
+  a.sA0 = d.sA0; a.sA1 = d.sA1; a.sB0 = d.sB0; a.sB1 = d.sB1; a.sC0 = d.sC0; a.sC1 = d.sC1;
+  const int64_t tiles = (int64_t)a.tiles_m * a.tiles_n;
+  if (tiles > (1 << 28)) return fail(MTF_ERR_UNSUPPORTED, "too many tiles");
+  dim3 grid((unsigned)(ceil_div(tiles, 8) * 8), (unsigned)(d.batch0 * d.batch1), 1);
+  if (d.a_kcontig && d.b_kcontig) return launch_layout<true, true>(d, a, grid, stream);
+  if (d.a_kcontig) return launch_layout<true, false>(d, a, grid, stream);
+  if (d.b_kcontig) return launch_layout<false, true>(d, a, grid, stream);
+  return launch_layout<false, false>(d, a, grid, stream);
+}
+
+}  // namespace mtf
