@@ -1,0 +1,204 @@
+#!/usr/bin/env python3
+"""Benchmark of the per-processor lowered-einsum path on one MI355X.
+
+One step = one pass of the whole hot path over one batch of synthetic input: forward and
+backward of a full Transformer-layer shard (attention + feed-forward sublayers with their
+residual adds), every contraction in the library's HIP kernels.  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload layer|ffn|mha]
+"""
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA, published
+METRIC = "TFLOP/s per-shard Transformer einsum (bf16) + % of MFMA peak on 1 MI355X"
+
+
+def flops_ffn(T, D, F):
+    return 2 * 2.0 * T * D * F                       # two einsums
+
+
+def flops_mha(B, L, D, H, K, causal):
+    T = B * L
+    pairs = L * (L + 1) / 2 if causal else L * L
+    return 4 * 2.0 * T * D * H * K + 2 * 2.0 * B * H * pairs * K     # q,k,v,o projections + 2 attention einsums
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="layer", choices=["layer", "ffn", "mha"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (one processor's share of the mesh); "
+              "--gpus must be 1", file=sys.stderr)
+        return 2
+
+    import torch
+    import mtf_inputs
+    import paper_1811_02084_amd as mtf
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    # ---------------------------------------------------------------- workload
+    if args.workload == "layer":
+        cfg = mtf_inputs.config5()
+        B, L, D = cfg["x"].shape
+        H, K, F = cfg["w_q"].shape[1], cfg["w_q"].shape[2], cfg["w_in"].shape[1]
+        causal = True
+        fwd = flops_mha(B, L, D, H, K, causal) + flops_ffn(B * L, D, F)
+        name = (f"config 5: full layer shard fwd+bwd, x[{B},{L},{D}] heads_local={H} d_k={K} "
+                f"d_ff_local={F} causal")
+        g = {k: (v.to(dev) if torch.is_tensor(v) else v) for k, v in cfg.items()}
+        w = {k: g[k] for k in ("w_q", "w_k", "w_v", "w_o", "w_in", "w_out")}
+        bufs = mtf.layer_alloc(g["x"], w)
+
+        def step():
+            mtf.layer_fwd(g["x"], w, cfg["scale"], causal, bufs)
+            mtf.layer_bwd(g["x"], w, bufs["saved"], g["dz"], cfg["scale"], causal, bufs)
+    elif args.workload == "ffn":
+        cfg = mtf_inputs.config2()
+        B, L, D = cfg["x"].shape
+        F = cfg["w_in"].shape[1]
+        fwd = flops_ffn(B * L, D, F)
+        name = f"config 2: FFN shard fwd+bwd, x[{B},{L},{D}] d_ff_local={F}"
+        g = {k: v.to(dev) for k, v in cfg.items()}
+        ws = torch.empty(B * L * F * 2 + 256, dtype=torch.uint8, device=dev)
+
+        def step():
+            a, _ = mtf.ffn_fwd(g["x"], g["w_in"], g["w_out"])
+            mtf.ffn_bwd(g["x"], a, g["w_in"], g["w_out"], g["dy"], workspace=ws)
+    else:
+        cfg = mtf_inputs.config3()
+        B, L, D = cfg["x"].shape
+        H, K = cfg["w_q"].shape[1], cfg["w_q"].shape[2]
+        causal = cfg["causal"]
+        fwd = flops_mha(B, L, D, H, K, causal)
+        name = f"config 3: attention shard fwd+bwd, x[{B},{L},{D}] heads_local={H} d_k={K}"
+        g = {k: (v.to(dev) if torch.is_tensor(v) else v) for k, v in cfg.items()}
+
+        def step():
+            r = mtf.mha_fwd(g["x"], g["w_q"], g["w_k"], g["w_v"], g["w_o"], cfg["scale"], causal)
+            mtf.mha_bwd(g["x"], g["w_q"], g["w_k"], g["w_v"], g["w_o"], r["q"], r["k"], r["v"], r["ctx"],
+                        r["lse"], g["dy"], cfg["scale"], causal)
+    step_flops = 3.0 * fwd          # every forward einsum has two gradient einsums of the same size
+
+    # ---------------------------------------------------------------- timed region
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed * 1e3 / args.steps
+    tflops = step_flops / (ms_per_step * 1e-3) / 1e12
+
+    # ---------------------------------------------------------------- dominant kernel, timed per launch
+    # same steps again with every launch bracketed by HIP events on the launch stream
+    mtf.timing_enable(True)
+    for _ in range(args.steps):
+        step()
+    kinds = mtf.timing_collect()
+    mtf.timing_enable(False)
+    kinds.sort(key=lambda r: -r["total_ms"])
+    dom = kinds[0]
+    avg_ms = dom["total_ms"] / dom["launches"]
+    achieved = dom["flops"] / dom["launches"] / (avg_ms * 1e-3) / 1e12
+    roofline = dict(bound="mfma", achieved=round(achieved, 1), peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
+                    frac=round(achieved / PEAK_BF16_TFLOPS, 4), traffic=None,
+                    kernel=dom["kernel"], launches_per_step=dom["launches"] // args.steps,
+                    avg_launch_us=round(avg_ms * 1e3, 2))
+    all_ms = sum(r["total_ms"] for r in kinds)
+    gemm = [r for r in kinds if r["kernel"].startswith("gemm_bf16_kernel")]
+    breakdown = {r["kernel"]: dict(us_per_step=round(r["total_ms"] * 1e3 / args.steps, 1),
+                                   launches_per_step=r["launches"] // args.steps,
+                                   tflops=round(r["flops"] / (r["total_ms"] * 1e-3) / 1e12, 1) if r["flops"] else None,
+                                   gbs=round(r["bytes"] / (r["total_ms"] * 1e-3) / 1e9, 1) if r["bytes"] else None)
+                 for r in kinds}
+    gemm_tflops = sum(r["flops"] for r in gemm) / (sum(r["total_ms"] for r in gemm) * 1e-3) / 1e12 if gemm else None
+
+    # ---------------------------------------------------------------- oracle on the host cores
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(args.workload, cfg)
+
+    out = {
+        "metric": METRIC, "value": round(tflops, 2), "unit": "TFLOP/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": name, "flop_per_step": step_flops,
+                   "flop_counting": "2 x iteration-space size per einsum, causal pairs only"},
+        "frac_of_bf16_mfma_peak": round(tflops / PEAK_BF16_TFLOPS, 4),
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "kernels": breakdown,
+        "all_gemm_launches_tflops": round(gemm_tflops, 1) if gemm_tflops else None,
+        "kernel_time_ms_per_step": round(all_ms / args.steps, 4),
+    }
+    print(json.dumps(out))
+    return 0
+
+
+def cpu_baseline(workload, cfg):
+    """The oracle as it stands, timed on a bounded sample of the same workload."""
+    import numpy as np
+    import torch
+    from threadpoolctl import threadpool_info
+    from oracle import layer as OL
+    from oracle.einsum import NT
+    from oracle.layer import B, L, D, F, H, K, V
+
+    f64 = lambda t: t.double().numpy()
+    nb = 2                                           # batch elements in the sample
+    x = NT(f64(cfg["x"][:nb]), (B, L, D))
+    t0 = time.perf_counter()
+    if workload == "ffn":
+        w_in, w_out = NT(f64(cfg["w_in"]), (D, F)), NT(f64(cfg["w_out"]), (F, D))
+        dy = NT(f64(cfg["dy"][:nb]), (B, L, D))
+        f = OL.ffn_fwd(x, w_in, w_out)
+        OL.ffn_bwd(x, f["a"], w_in, w_out, dy)
+        T = nb * cfg["x"].shape[1]
+        flops = 3 * flops_ffn(T, cfg["x"].shape[2], cfg["w_in"].shape[1])
+    else:
+        names = dict(w_q=(D, H, K), w_k=(D, H, K), w_v=(D, H, V), w_o=(H, V, D), w_in=(D, F), w_out=(F, D))
+        w = {k: NT(f64(cfg[k]), names[k]) for k in names if k in cfg}
+        causal = bool(cfg.get("causal", False))
+        Bq, Lq, Dq = nb, cfg["x"].shape[1], cfg["x"].shape[2]
+        Hq, Kq = cfg["w_q"].shape[1], cfg["w_q"].shape[2]
+        if workload == "layer":
+            dz = NT(f64(cfg["dz"][:nb]), (B, L, D))
+            f = OL.layer_fwd(x, w, cfg["scale"], causal)
+            OL.layer_bwd(x, w, f["saved"], dz, cfg["scale"], causal)
+            flops = 3 * (flops_mha(Bq, Lq, Dq, Hq, Kq, causal) + flops_ffn(Bq * Lq, Dq, cfg["w_in"].shape[1]))
+        else:
+            dy = NT(f64(cfg["dy"][:nb]), (B, L, D))
+            f = OL.mha_fwd(x, w["w_q"], w["w_k"], w["w_v"], w["w_o"], cfg["scale"], causal)
+            OL.mha_bwd(x, w["w_q"], w["w_k"], w["w_v"], w["w_o"], f["q"], f["k"], f["v"], f["ctx"], f["lse"],
+                       dy, cfg["scale"], causal)
+            flops = 3 * flops_mha(Bq, Lq, Dq, Hq, Kq, causal)
+    dt = time.perf_counter() - t0
+    threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    return {"value": round(flops / dt / 1e12, 4), "unit": "TFLOP/s", "cores": threads, "kind": "oracle",
+            "sample": f"first {nb} of {cfg['x'].shape[0]} batch elements, forward + backward, fp64 "
+                      f"(numpy; {dt:.1f} s)"}
+
+
+if __name__ == "__main__":
+    sys.exit(main())

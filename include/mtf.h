@@ -11,8 +11,10 @@
  *
  * Conventions (all entry points)
  *   - Return value: MTF_OK (0) or a negative mtf_status.  Nothing throws or aborts across the
- *     ABI.  On error no output buffer has been written by the failing call (host outputs are
- *     untouched; no kernel has been launched).  mtf_last_error() gives a thread-local text.
+ *     ABI.  Arguments are validated before anything is written or launched, so every error
+ *     except MTF_ERR_HIP leaves all outputs untouched; MTF_ERR_HIP (a failed launch in the
+ *     middle of a multi-kernel step) may leave device outputs partly written.
+ *     mtf_last_error() gives a thread-local text.
  *   - Tensors are dense, row-major in the order their dims are listed, 16-byte aligned.
  *   - "host" pointers are ordinary memory; "device" pointers are HIP device memory owned by
  *     the caller.  The library never allocates or frees device memory; scratch comes in
@@ -221,6 +223,25 @@ int mtf_layer_bwd(const mtf_layer_dims* d, const void* x, const mtf_layer_weight
                   const mtf_layer_saved* saved, const void* dz, float scale, int causal,
                   const mtf_layer_grads* g, void* dx, void* workspace, size_t workspace_bytes,
                   void* stream);
+
+/* ---------------------------------------------------------------- measurement aid
+ * While enabled, every kernel launch of the library is bracketed by two HIP events recorded on
+ * the launch's own stream.  mtf_timing_collect() waits for those events (it synchronises with the
+ * work that was timed), adds them up per kernel and forgets them.  For callers that must report
+ * per-kernel time measured inside their own timed region (the benchmark); leave it off otherwise.
+ * flops / bytes are the algorithmic work of the timed launches: 2 x iteration-space size for a
+ * contraction (Appendix B), bytes of inputs + outputs for the HBM-bound helpers. */
+typedef struct {
+  char kernel[96];   /* kernel name as a profiler prints it, NUL-terminated */
+  int64_t launches;
+  double total_ms;
+  double flops;
+  double bytes;
+} mtf_kernel_time;
+
+int mtf_timing_enable(int on);
+/* out: host array of max_kinds entries; *n_kinds receives the number filled. */
+int mtf_timing_collect(mtf_kernel_time* out, int32_t max_kinds, int32_t* n_kinds);
 
 #ifdef __cplusplus
 }

@@ -259,3 +259,128 @@ def cast(x, dtype):
     out = torch.empty(x.shape, dtype=dtype, device=x.device)
     _check(lib.mtf_cast(_ptr(x), _dt(x), _ptr(out), _dt(out), C.c_int64(x.numel()), _stream()))
     return out
+
+
+# ------------------------------------------------------------------ fixed layer steps
+def _ws(nbytes, device):
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
+def ffn_fwd(x, w_in, w_out):
+    """x[batch,length,d_model], w_in[d_model,d_ff], w_out[d_ff,d_model] (bf16) ->
+    (a bf16 [batch,length,d_ff], y_partial fp32 [batch,length,d_model])."""
+    b, l, dm = x.shape
+    d = mtf_ffn_dims(b, l, dm, w_in.shape[1])
+    a = torch.empty((b, l, w_in.shape[1]), dtype=torch.bfloat16, device=x.device)
+    y = torch.empty((b, l, dm), dtype=torch.float32, device=x.device)
+    _check(lib.mtf_ffn_fwd(C.byref(d), _ptr(x), _ptr(w_in), _ptr(w_out), _ptr(a), _ptr(y), _stream()))
+    return a, y
+
+
+def ffn_bwd(x, a, w_in, w_out, dy, workspace=None):
+    b, l, dm = x.shape
+    d = mtf_ffn_dims(b, l, dm, w_in.shape[1])
+    need = lib.mtf_ffn_bwd_workspace_bytes(C.byref(d))
+    ws = workspace if workspace is not None else _ws(need, x.device)
+    dw_in = torch.empty(w_in.shape, dtype=torch.float32, device=x.device)
+    dw_out = torch.empty(w_out.shape, dtype=torch.float32, device=x.device)
+    dx = torch.empty(x.shape, dtype=torch.float32, device=x.device)
+    _check(lib.mtf_ffn_bwd(C.byref(d), _ptr(x), _ptr(a), _ptr(w_in), _ptr(w_out), _ptr(dy), _ptr(dw_in),
+                           _ptr(dw_out), _ptr(dx), _ptr(ws), C.c_size_t(ws.numel()), _stream()))
+    return dict(dw_in=dw_in, dw_out=dw_out, dx=dx)
+
+
+def mha_fwd(x, w_q, w_k, w_v, w_o, scale, causal):
+    b, l, dm = x.shape
+    h, dk = w_q.shape[1], w_q.shape[2]
+    d = mtf_mha_dims(b, l, dm, h, dk)
+    mk = lambda: torch.empty((b, l, h, dk), dtype=torch.bfloat16, device=x.device)
+    q, k, v, ctx = mk(), mk(), mk(), mk()
+    lse = torch.empty((b, h, l), dtype=torch.float32, device=x.device)
+    y = torch.empty((b, l, dm), dtype=torch.float32, device=x.device)
+    _check(lib.mtf_mha_fwd(C.byref(d), _ptr(x), _ptr(w_q), _ptr(w_k), _ptr(w_v), _ptr(w_o),
+                           C.c_float(scale), int(bool(causal)), _ptr(q), _ptr(k), _ptr(v), _ptr(ctx),
+                           _ptr(lse), _ptr(y), _stream()))
+    return dict(q=q, k=k, v=v, ctx=ctx, lse=lse, y=y)
+
+
+def mha_bwd(x, w_q, w_k, w_v, w_o, q, k, v, ctx, lse, dy, scale, causal, workspace=None):
+    b, l, dm = x.shape
+    h, dk = w_q.shape[1], w_q.shape[2]
+    d = mtf_mha_dims(b, l, dm, h, dk)
+    need = lib.mtf_mha_bwd_workspace_bytes(C.byref(d))
+    ws = workspace if workspace is not None else _ws(need, x.device)
+    f32 = lambda t: torch.empty(t.shape, dtype=torch.float32, device=x.device)
+    out = dict(dw_q=f32(w_q), dw_k=f32(w_k), dw_v=f32(w_v), dw_o=f32(w_o), dx=f32(x))
+    _check(lib.mtf_mha_bwd(C.byref(d), _ptr(x), _ptr(w_q), _ptr(w_k), _ptr(w_v), _ptr(w_o), _ptr(q),
+                           _ptr(k), _ptr(v), _ptr(ctx), _ptr(lse), _ptr(dy), C.c_float(scale),
+                           int(bool(causal)), _ptr(out["dw_q"]), _ptr(out["dw_k"]), _ptr(out["dw_v"]),
+                           _ptr(out["dw_o"]), _ptr(out["dx"]), _ptr(ws), C.c_size_t(ws.numel()), _stream()))
+    return out
+
+
+def _layer_dims(x, w):
+    b, l, dm = x.shape
+    return mtf_layer_dims(b, l, dm, w["w_q"].shape[1], w["w_q"].shape[2], w["w_in"].shape[1])
+
+
+def _weights(w):
+    return mtf_layer_weights(*[w[n].data_ptr() for n in ("w_q", "w_k", "w_v", "w_o", "w_in", "w_out")])
+
+
+def layer_alloc(x, w):
+    """Buffers a layer step needs, allocated once (saved activations, grads, workspaces)."""
+    b, l, dm = x.shape
+    h, dk, f = w["w_q"].shape[1], w["w_q"].shape[2], w["w_in"].shape[1]
+    dev = x.device
+    d = _layer_dims(x, w)
+    bf = lambda *s: torch.empty(s, dtype=torch.bfloat16, device=dev)
+    saved = dict(q=bf(b, l, h, dk), k=bf(b, l, h, dk), v=bf(b, l, h, dk), ctx=bf(b, l, h, dk),
+                 lse=torch.empty((b, h, l), dtype=torch.float32, device=dev), u=bf(b, l, dm), a=bf(b, l, f))
+    grads = {"d" + n: torch.empty(w[n].shape, dtype=torch.float32, device=dev)
+             for n in ("w_q", "w_k", "w_v", "w_o", "w_in", "w_out")}
+    return dict(saved=saved, grads=grads, z=bf(b, l, dm), dx=bf(b, l, dm),
+                ws_fwd=_ws(lib.mtf_layer_fwd_workspace_bytes(C.byref(d)), dev),
+                ws_bwd=_ws(lib.mtf_layer_bwd_workspace_bytes(C.byref(d)), dev))
+
+
+def _saved(s):
+    return mtf_layer_saved(*[s[n].data_ptr() for n in ("q", "k", "v", "ctx", "lse", "u", "a")])
+
+
+def layer_fwd(x, w, scale, causal, bufs):
+    d = _layer_dims(x, w)
+    ww, sv = _weights(w), _saved(bufs["saved"])
+    _check(lib.mtf_layer_fwd(C.byref(d), _ptr(x), C.byref(ww), C.c_float(scale), int(bool(causal)),
+                             C.byref(sv), _ptr(bufs["z"]), _ptr(bufs["ws_fwd"]),
+                             C.c_size_t(bufs["ws_fwd"].numel()), _stream()))
+    return bufs["z"]
+
+
+def layer_bwd(x, w, saved, dz, scale, causal, bufs):
+    d = _layer_dims(x, w)
+    ww, sv = _weights(w), _saved(saved)
+    g = mtf_layer_grads(*[bufs["grads"][n].data_ptr() for n in ("dw_q", "dw_k", "dw_v", "dw_o", "dw_in", "dw_out")])
+    _check(lib.mtf_layer_bwd(C.byref(d), _ptr(x), C.byref(ww), C.byref(sv), _ptr(dz), C.c_float(scale),
+                             int(bool(causal)), C.byref(g), _ptr(bufs["dx"]), _ptr(bufs["ws_bwd"]),
+                             C.c_size_t(bufs["ws_bwd"].numel()), _stream()))
+    return bufs["dx"]
+
+
+# ------------------------------------------------------------------ measurement aid
+class mtf_kernel_time(C.Structure):
+    _fields_ = [("kernel", C.c_char * 96), ("launches", C.c_int64), ("total_ms", C.c_double),
+                ("flops", C.c_double), ("bytes", C.c_double)]
+
+
+def timing_enable(on):
+    _check(lib.mtf_timing_enable(1 if on else 0))
+
+
+def timing_collect(max_kinds=64):
+    """Per-kernel totals of the launches made while timing was enabled (synchronises)."""
+    arr = (mtf_kernel_time * max_kinds)()
+    n = C.c_int32()
+    _check(lib.mtf_timing_collect(arr, max_kinds, C.byref(n)))
+    return [dict(kernel=arr[i].kernel.decode(), launches=arr[i].launches, total_ms=arr[i].total_ms,
+                 flops=arr[i].flops, bytes=arr[i].bytes) for i in range(n.value)]

@@ -1,0 +1,506 @@
+// Fused softmax attention for one processor's heads: the two attention einsums
+//   logits[b,h,l,m] = einsum(q[b,l,h,k], k_[b,m,h,k])      ctx[b,l,h,v] = einsum(p[b,h,l,m], v_[b,m,h,v])
+// with the row softmax between them, forward and backward, without materialising [l,m] tensors.
+// The memory_length dim is never split (softmax needs the whole row locally), heads are.
+//
+// All matrix products run on v_mfma_f32_32x32x16_bf16.  Orientation trick used throughout: the
+// first product is computed TRANSPOSED relative to the second one's needs, so that the fp32
+// accumulator a lane holds (one column, 16 rows in the order (j/4)*8 + (lane/32)*4 + j%4) can be
+// packed to bf16 and fed straight back as the next MFMA's B operand; the other operand of that
+// second product is read with the LDS transpose load using the same row order.  No shuffles, no
+// round trip through LDS for the probabilities.
+//
+// LDS tiles are 64 rows x 128 d (256 B per row), filled by direct global->LDS loads.  One XOR
+// swizzle of the 16-byte chunk index serves both access patterns (row-wise ds_read_b128 and
+// transposed ds_read_b64_tr_b16).
+#include "attention.h"
+
+#include "timing.h"
+
+namespace mtf {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(4 * sizeof(short)))) short s16x4;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
+
+#define LDS_PTR(T, p) ((__attribute__((address_space(3))) T*)(p))
+
+namespace {
+
+constexpr int kRowBytes = kHeadDim * 2;       // 256
+constexpr int kTileRows = 64;
+constexpr int kTileBytes = kTileRows * kRowBytes;  // 16 KiB
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+struct AttnArgs {
+  const bf16_t *q, *k, *v, *ctx, *dctx;
+  bf16_t *out0, *out1;  // fwd: ctx | dq kernel: dq | dkv kernel: dk, dv
+  const float *lse_in, *delta_in;
+  float* lse_out;
+  int batch, length, heads;
+  float scale;
+  int causal;
+};
+
+__device__ __forceinline__ uint32_t lds_address(const char* p) {
+  return (uint32_t)(uintptr_t)LDS_PTR(const char, p);
+}
+
+// 16 bytes per lane, global -> LDS, lane i to lds_addr + 16*i (inline asm: the waits are placed
+// by hand; m0 carries the LDS address and is used by nothing else here).
+__device__ __forceinline__ void load16_to_lds(const char* uniform_base, uint32_t lane_offset,
+                                              uint32_t lds_addr_uniform) {
+  asm volatile(
+      "s_mov_b32 m0, %0\n\t"
+      "s_nop 0\n\t"
+      "global_load_lds_dwordx4 %1, %2\n"
+      :
+      : "s"(lds_addr_uniform), "v"(lane_offset), "s"(uniform_base)
+      : "memory", "m0");
+}
+
+__device__ __forceinline__ void wait_loads_then_barrier() {
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+}
+
+// chunk c of row r is stored at chunk c ^ swz(r): a bijection over any 16 consecutive rows (row
+// reads of 16 lanes hit 16 different chunks) whose upper two bits differ over any aligned group
+// of 4 rows (transpose reads of 4 rows hit 4 different 64-byte bank groups).
+__device__ __forceinline__ int swz(int row) { return ((row & 3) << 2) | ((row >> 2) & 3); }
+
+// Tile <- rows row0 .. row0+63 (clamped to row_limit-1) of head h of a [*, rows, heads, 128] tensor.
+// base: address of element (b, 0, h, 0).
+template <int NWAVES>
+__device__ __forceinline__ void load_tile(const bf16_t* base, uint32_t row_stride_bytes, int row0,
+                                          int row_limit, char* tile, int wave, int lane) {
+#pragma unroll
+  for (int i = 0; i < 16 / NWAVES; ++i) {
+    const int run = i * NWAVES + wave;
+    const int row = run * 4 + (lane >> 4);
+    const int c = (lane & 15) ^ swz(row);
+    const int src = min(row0 + row, row_limit - 1);
+    load16_to_lds(reinterpret_cast<const char*>(base), (uint32_t)src * row_stride_bytes + c * 16,
+                  lds_address(tile) + run * 1024);
+  }
+}
+
+// Operand fragment with the tile's rows as the MFMA's outer (M or N) index and d as k:
+// lane l -> row row_base + l%32, d = ks*16 + (l/32)*8 + 0..7.
+__device__ __forceinline__ bf16x8 rows_frag(const char* tile, int row_base, int ks, int lane) {
+  const int r = row_base + (lane & 31);
+  const int c = ks * 2 + (lane >> 5);
+  return *LDS_PTR(const bf16x8, tile + r * kRowBytes + ((c ^ swz(r)) << 4));
+}
+
+// Operand fragment with d as the MFMA's outer index (32 columns from d_base) and the tile's rows
+// as k, in accumulator row order: k-slot e of lane-half hf is row row_base + (e/4)*8 + hf*4 + e%4.
+__device__ __forceinline__ bf16x8 cols_frag(const char* tile, int d_base, int row_base, int lane) {
+  const int g = lane >> 4, j = lane & 15;
+  const int d = d_base + (g & 1) * 16 + (j & 3) * 4;
+  const int row = row_base + (g >> 1) * 4 + (j >> 2);
+  union {
+    s16x4 h[2];
+    bf16x8 v;
+  } u;
+#pragma unroll
+  for (int h2 = 0; h2 < 2; ++h2) {
+    const int r = row + h2 * 8;
+    const char* p = tile + r * kRowBytes + (((d >> 3) ^ swz(r)) << 4) + (d & 7) * 2;
+    u.h[h2] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, p));
+  }
+  return u.v;
+}
+
+// Same row-operand fragment straight from global memory (kept in registers for the whole kernel).
+__device__ __forceinline__ bf16x8 global_rows_frag(const bf16_t* base, int64_t row_stride, int row,
+                                                   int ks, int lane) {
+  return *reinterpret_cast<const bf16x8*>(base + (int64_t)row * row_stride + ks * 16 + (lane >> 5) * 8);
+}
+
+__device__ __forceinline__ bf16x8 pack8(const float* v) {
+  union {
+    uint32_t w[4];
+    bf16x8 v;
+  } u;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) u.w[i] = pack_bf16x2(v[2 * i], v[2 * i + 1]);
+  return u.v;
+}
+
+__device__ __forceinline__ f32x16 zero16() {
+  f32x16 z;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) z[i] = 0.f;
+  return z;
+}
+
+// Row of an accumulator value: value jj of a lane in half hf sits at row (jj/4)*8 + hf*4 + jj%4.
+__device__ __forceinline__ int acc_row(int jj, int hf) { return (jj >> 2) * 8 + hf * 4 + (jj & 3); }
+
+// Stores a [32 x 128]^T accumulator set (lane = one row of the output, 4 consecutive d per group)
+// as bf16 rows of a [*, rows, heads, 128] tensor.
+__device__ __forceinline__ void store_rows_bf16(bf16_t* base, int64_t row_stride, int row,
+                                                int row_limit, const f32x16* acc, float mul,
+                                                int lane) {
+  if (row >= row_limit) return;
+  const int hf = lane >> 5;
+#pragma unroll
+  for (int blk = 0; blk < 4; ++blk)
+#pragma unroll
+    for (int q4 = 0; q4 < 4; ++q4) {
+      const int d = blk * 32 + q4 * 8 + hf * 4;
+      uint2 w = make_uint2(pack_bf16x2(acc[blk][q4 * 4 + 0] * mul, acc[blk][q4 * 4 + 1] * mul),
+                           pack_bf16x2(acc[blk][q4 * 4 + 2] * mul, acc[blk][q4 * 4 + 3] * mul));
+      *reinterpret_cast<uint2*>(base + (int64_t)row * row_stride + d) = w;
+    }
+}
+
+// ------------------------------------------------------------------------------------ forward
+// One workgroup: NWAVES*32 query rows of one (batch, head); each wave owns 32 of them.
+template <int NWAVES>
+__global__ void __launch_bounds__(NWAVES * 64) attn_fwd_kernel(AttnArgs a) {
+  __shared__ __attribute__((aligned(1024))) char k_tile[kTileBytes];
+  __shared__ __attribute__((aligned(1024))) char v_tile[kTileBytes];
+  const int lane = threadIdx.x & 63, hf = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int L = a.length, H = a.heads;
+  const int b = blockIdx.z, h = blockIdx.y;
+  const int q0 = blockIdx.x * (NWAVES * 32);
+  const int64_t rs = (int64_t)H * kHeadDim;
+  const int64_t head0 = ((int64_t)b * L) * rs + (int64_t)h * kHeadDim;
+  const bf16_t *qb = a.q + head0, *kb = a.k + head0, *vb = a.v + head0;
+
+  const int q_lane = q0 + wave * 32 + (lane & 31);  // this lane's query row
+  const int q_load = min(q_lane, L - 1);
+  bf16x8 qf[8];
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) qf[ks] = global_rows_frag(qb, rs, q_load, ks, lane);
+
+  f32x16 o[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) o[i] = zero16();
+  float m2 = -INFINITY, lsum = 0.f;  // running max (log2 units) and row sum
+  const float c2 = a.scale * kLog2e;
+
+  const int kv_end = a.causal ? min(L, q0 + NWAVES * 32) : L;
+  for (int kv0 = 0; kv0 < kv_end; kv0 += kTileRows) {
+    __syncthreads();  // everyone is done with the previous tiles
+    load_tile<NWAVES>(kb, (uint32_t)(rs * 2), kv0, L, k_tile, wave, lane);
+    load_tile<NWAVES>(vb, (uint32_t)(rs * 2), kv0, L, v_tile, wave, lane);
+    wait_loads_then_barrier();
+    if (a.causal && kv0 > q0 + wave * 32 + 31) continue;  // nothing visible for this wave
+
+    // logits^T: rows = memory positions of the tile, column = this lane's query
+    f32x16 s[2];
+#pragma unroll
+    for (int kvb = 0; kvb < 2; ++kvb) {
+      s[kvb] = zero16();
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks)
+        s[kvb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rows_frag(k_tile, kvb * 32, ks, lane), qf[ks],
+                                                         s[kvb], 0, 0, 0);
+    }
+    float mx = -INFINITY;
+#pragma unroll
+    for (int kvb = 0; kvb < 2; ++kvb)
+#pragma unroll
+      for (int jj = 0; jj < 16; ++jj) {
+        const int kv = kv0 + kvb * 32 + acc_row(jj, hf);
+        const bool vis = kv < L && (!a.causal || kv <= q_lane);
+        const float x = vis ? s[kvb][jj] * c2 : -INFINITY;
+        s[kvb][jj] = x;
+        mx = fmaxf(mx, x);
+      }
+    mx = fmaxf(mx, __shfl_xor(mx, 32));  // the other half-wave holds the rest of this query's row
+    const float m_new = fmaxf(m2, mx);   // finite: tile 0 always shows position 0
+    const float alpha = __builtin_amdgcn_exp2f(m2 - m_new);
+    float psum = 0.f;
+    bf16x8 pf[4];
+#pragma unroll
+    for (int kvb = 0; kvb < 2; ++kvb) {
+      float p[16];
+#pragma unroll
+      for (int jj = 0; jj < 16; ++jj) {
+        p[jj] = __builtin_amdgcn_exp2f(s[kvb][jj] - m_new);  // exp2(-inf) = 0 for hidden positions
+        psum += p[jj];
+      }
+      pf[kvb * 2 + 0] = pack8(p);
+      pf[kvb * 2 + 1] = pack8(p + 8);
+    }
+    psum += __shfl_xor(psum, 32);
+    lsum = lsum * alpha + psum;
+    m2 = m_new;
+#pragma unroll
+    for (int blk = 0; blk < 4; ++blk) {
+#pragma unroll
+      for (int e = 0; e < 16; ++e) o[blk][e] *= alpha;
+#pragma unroll
+      for (int t = 0; t < 4; ++t)
+        o[blk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cols_frag(v_tile, blk * 32, t * 16, lane), pf[t],
+                                                         o[blk], 0, 0, 0);
+    }
+  }
+  store_rows_bf16(a.out0 + head0, rs, q_lane, L, o, 1.f / lsum, lane);
+  if (q_lane < L && hf == 0)
+    a.lse_out[((int64_t)b * H + h) * L + q_lane] = (m2 + __log2f(lsum)) * kLn2;
+}
+
+// ------------------------------------------------------------------------------------ backward
+// delta[b,h,l] = sum_d dctx[b,l,h,d] * ctx[b,l,h,d]  (= sum_m p * dp of the softmax Jacobian)
+__global__ void __launch_bounds__(256) attn_delta_kernel(const bf16_t* __restrict__ ctx,
+                                                        const bf16_t* __restrict__ dctx,
+                                                        float* __restrict__ delta, int batch,
+                                                        int length, int heads) {
+  const int64_t rows = (int64_t)batch * length * heads;  // (b, l, h) in memory order
+  const int64_t row = blockIdx.x * 16 + (threadIdx.x >> 4);
+  const int sub = threadIdx.x & 15;
+  float acc = 0.f;
+  if (row < rows) {
+    const uint4 x = *reinterpret_cast<const uint4*>(ctx + row * kHeadDim + sub * 8);
+    const uint4 y = *reinterpret_cast<const uint4*>(dctx + row * kHeadDim + sub * 8);
+    const uint32_t xs[4] = {x.x, x.y, x.z, x.w}, ys[4] = {y.x, y.y, y.z, y.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      acc = fmaf(__uint_as_float(xs[i] << 16), __uint_as_float(ys[i] << 16), acc);
+      acc = fmaf(__uint_as_float(xs[i] & 0xffff0000u), __uint_as_float(ys[i] & 0xffff0000u), acc);
+    }
+  }
+#pragma unroll
+  for (int m = 8; m >= 1; m >>= 1) acc += __shfl_xor(acc, m);
+  if (row < rows && sub == 0) {
+    const int64_t h = row % heads, l = (row / heads) % length, b = row / ((int64_t)heads * length);
+    delta[(b * heads + h) * length + l] = acc;
+  }
+}
+
+// dq: one workgroup per NWAVES*32 query rows; loops over memory tiles.
+template <int NWAVES>
+__global__ void __launch_bounds__(NWAVES * 64) attn_dq_kernel(AttnArgs a) {
+  __shared__ __attribute__((aligned(1024))) char k_tile[kTileBytes];
+  __shared__ __attribute__((aligned(1024))) char v_tile[kTileBytes];
+  const int lane = threadIdx.x & 63, hf = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int L = a.length, H = a.heads;
+  const int b = blockIdx.z, h = blockIdx.y;
+  const int q0 = blockIdx.x * (NWAVES * 32);
+  const int64_t rs = (int64_t)H * kHeadDim;
+  const int64_t head0 = ((int64_t)b * L) * rs + (int64_t)h * kHeadDim;
+  const bf16_t *qb = a.q + head0, *kb = a.k + head0, *vb = a.v + head0, *dob = a.dctx + head0;
+
+  const int q_lane = q0 + wave * 32 + (lane & 31);
+  const int q_load = min(q_lane, L - 1);
+  bf16x8 qf[8], dof[8];
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) {
+    qf[ks] = global_rows_frag(qb, rs, q_load, ks, lane);
+    dof[ks] = global_rows_frag(dob, rs, q_load, ks, lane);
+  }
+  const int64_t stat = ((int64_t)b * H + h) * L + q_load;
+  const float lse2 = a.lse_in[stat] * kLog2e, dl = a.delta_in[stat];
+  const float c2 = a.scale * kLog2e;
+
+  f32x16 dq[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) dq[i] = zero16();
+
+  const int kv_end = a.causal ? min(L, q0 + NWAVES * 32) : L;
+  for (int kv0 = 0; kv0 < kv_end; kv0 += kTileRows) {
+    __syncthreads();
+    load_tile<NWAVES>(kb, (uint32_t)(rs * 2), kv0, L, k_tile, wave, lane);
+    load_tile<NWAVES>(vb, (uint32_t)(rs * 2), kv0, L, v_tile, wave, lane);
+    wait_loads_then_barrier();
+    if (a.causal && kv0 > q0 + wave * 32 + 31) continue;
+
+    bf16x8 dsf[4];
+#pragma unroll
+    for (int kvb = 0; kvb < 2; ++kvb) {
+      f32x16 s = zero16(), dp = zero16();
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) {
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rows_frag(k_tile, kvb * 32, ks, lane), qf[ks], s, 0, 0, 0);
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rows_frag(v_tile, kvb * 32, ks, lane), dof[ks], dp, 0, 0, 0);
+      }
+      float ds[16];
+#pragma unroll
+      for (int jj = 0; jj < 16; ++jj) {
+        const int kv = kv0 + kvb * 32 + acc_row(jj, hf);
+        const bool vis = kv < L && (!a.causal || kv <= q_lane);
+        const float p = __builtin_amdgcn_exp2f(s[jj] * c2 - lse2);
+        ds[jj] = vis ? p * (dp[jj] - dl) * a.scale : 0.f;
+      }
+      dsf[kvb * 2 + 0] = pack8(ds);
+      dsf[kvb * 2 + 1] = pack8(ds + 8);
+    }
+#pragma unroll
+    for (int blk = 0; blk < 4; ++blk)
+#pragma unroll
+      for (int t = 0; t < 4; ++t)
+        dq[blk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cols_frag(k_tile, blk * 32, t * 16, lane), dsf[t],
+                                                          dq[blk], 0, 0, 0);
+  }
+  store_rows_bf16(a.out0 + head0, rs, q_lane, L, dq, 1.f, lane);
+}
+
+// dk, dv: one workgroup per NWAVES*32 memory rows; loops over query tiles.
+template <int NWAVES>
+__global__ void __launch_bounds__(NWAVES * 64) attn_dkv_kernel(AttnArgs a) {
+  __shared__ __attribute__((aligned(1024))) char q_tile[kTileBytes];
+  __shared__ __attribute__((aligned(1024))) char do_tile[kTileBytes];
+  __shared__ __attribute__((aligned(16))) float lse_tile[kTileRows];
+  __shared__ __attribute__((aligned(16))) float delta_tile[kTileRows];
+  const int lane = threadIdx.x & 63, hf = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int L = a.length, H = a.heads;
+  const int b = blockIdx.z, h = blockIdx.y;
+  const int kvblk0 = blockIdx.x * (NWAVES * 32);
+  const int64_t rs = (int64_t)H * kHeadDim;
+  const int64_t head0 = ((int64_t)b * L) * rs + (int64_t)h * kHeadDim;
+  const bf16_t *qb = a.q + head0, *kb = a.k + head0, *vb = a.v + head0, *dob = a.dctx + head0;
+  const float* lse_row = a.lse_in + ((int64_t)b * H + h) * L;
+  const float* delta_row = a.delta_in + ((int64_t)b * H + h) * L;
+
+  const int kv_lane = kvblk0 + wave * 32 + (lane & 31);  // this lane's memory row
+  const int kv_load = min(kv_lane, L - 1);
+  bf16x8 kf[8], vf[8];
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) {
+    kf[ks] = global_rows_frag(kb, rs, kv_load, ks, lane);
+    vf[ks] = global_rows_frag(vb, rs, kv_load, ks, lane);
+  }
+  const float c2 = a.scale * kLog2e;
+  f32x16 dk[4], dv[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    dk[i] = zero16();
+    dv[i] = zero16();
+  }
+
+  const int q_begin = a.causal ? (kvblk0 / kTileRows) * kTileRows : 0;  // earlier queries see none of these rows
+  for (int q0 = q_begin; q0 < L; q0 += kTileRows) {
+    __syncthreads();
+    load_tile<NWAVES>(qb, (uint32_t)(rs * 2), q0, L, q_tile, wave, lane);
+    load_tile<NWAVES>(dob, (uint32_t)(rs * 2), q0, L, do_tile, wave, lane);
+    if (threadIdx.x < kTileRows) {
+      const int qi = min(q0 + (int)threadIdx.x, L - 1);
+      lse_tile[threadIdx.x] = lse_row[qi] * kLog2e;
+      delta_tile[threadIdx.x] = delta_row[qi];
+    }
+    wait_loads_then_barrier();
+    if (a.causal && q0 + kTileRows - 1 < kvblk0 + wave * 32) continue;  // all queries precede this wave's rows
+
+    bf16x8 pf[4], dsf[4];
+#pragma unroll
+    for (int qblk = 0; qblk < 2; ++qblk) {
+      f32x16 s = zero16(), dp = zero16();
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) {
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rows_frag(q_tile, qblk * 32, ks, lane), kf[ks], s, 0, 0, 0);
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rows_frag(do_tile, qblk * 32, ks, lane), vf[ks], dp, 0, 0, 0);
+      }
+      float p[16], ds[16];
+#pragma unroll
+      for (int g4 = 0; g4 < 4; ++g4) {
+        const int r0 = qblk * 32 + g4 * 8 + hf * 4;  // 4 consecutive query rows of this group
+        const f32x4 l4 = *LDS_PTR(const f32x4, reinterpret_cast<const char*>(lse_tile) + r0 * 4);
+        const f32x4 d4 = *LDS_PTR(const f32x4, reinterpret_cast<const char*>(delta_tile) + r0 * 4);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int jj = g4 * 4 + e;
+          const int qi = q0 + r0 + e;
+          const bool vis = qi < L && kv_lane < L && (!a.causal || kv_lane <= qi);
+          const float pe = vis ? __builtin_amdgcn_exp2f(s[jj] * c2 - l4[e]) : 0.f;
+          p[jj] = pe;
+          ds[jj] = vis ? pe * (dp[jj] - d4[e]) * a.scale : 0.f;
+        }
+      }
+      pf[qblk * 2 + 0] = pack8(p);
+      pf[qblk * 2 + 1] = pack8(p + 8);
+      dsf[qblk * 2 + 0] = pack8(ds);
+      dsf[qblk * 2 + 1] = pack8(ds + 8);
+    }
+#pragma unroll
+    for (int blk = 0; blk < 4; ++blk)
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        dv[blk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cols_frag(do_tile, blk * 32, t * 16, lane), pf[t],
+                                                          dv[blk], 0, 0, 0);
+        dk[blk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cols_frag(q_tile, blk * 32, t * 16, lane), dsf[t],
+                                                          dk[blk], 0, 0, 0);
+      }
+  }
+  store_rows_bf16(a.out0 + head0, rs, kv_lane, L, dk, 1.f, lane);
+  store_rows_bf16(a.out1 + head0, rs, kv_lane, L, dv, 1.f, lane);
+}
+
+int check_shape(const AttnShape& s) {
+  if (s.batch <= 0 || s.length <= 0 || s.heads <= 0)
+    return fail(MTF_ERR_SIZE_MISMATCH, "attention shape %d x %d x %d", s.batch, s.length, s.heads);
+  if (s.batch > 65535 || s.heads > 65535) return fail(MTF_ERR_UNSUPPORTED, "batch / heads > 65535");
+  if ((int64_t)s.length * s.heads * kRowBytes >= (int64_t)1 << 32)
+    return fail(MTF_ERR_UNSUPPORTED, "length * heads too large for 32-bit tile offsets");
+  return MTF_OK;
+}
+
+AttnArgs make_args(const AttnShape& s) {
+  AttnArgs a{};
+  a.batch = s.batch;
+  a.length = s.length;
+  a.heads = s.heads;
+  a.scale = s.scale;
+  a.causal = s.causal;
+  return a;
+}
+
+}  // namespace
+
+int attn_fwd_launch(const AttnShape& s, const bf16_t* q, const bf16_t* k, const bf16_t* v,
+                    bf16_t* ctx, float* lse, hipStream_t stream) {
+  if (int rc = check_shape(s)) return rc;
+  AttnArgs a = make_args(s);
+  a.q = q; a.k = k; a.v = v; a.out0 = ctx; a.lse_out = lse;
+  // 64 query rows per workgroup keeps >= 256 workgroups in flight at the shard sizes of interest
+  dim3 grid((unsigned)ceil_div(s.length, 64), (unsigned)s.heads, (unsigned)s.batch);
+  // algorithmic work: two contractions over the visible (l, m) pairs
+  const double pairs = s.causal ? 0.5 * s.length * (s.length + 1.0) : (double)s.length * s.length;
+  const double flops = 2.0 * 2.0 * s.batch * s.heads * pairs * kHeadDim;
+  const double bytes = 4.0 * s.batch * s.length * s.heads * kRowBytes;
+  LaunchTimer timer("attn_fwd_kernel<2>", flops, bytes, stream);
+  attn_fwd_kernel<2><<<grid, 128, 0, stream>>>(a);
+  return launch_status("attn_fwd_kernel");
+}
+
+int attn_bwd_launch(const AttnShape& s, const bf16_t* q, const bf16_t* k, const bf16_t* v,
+                    const bf16_t* ctx, const float* lse, const bf16_t* dctx, bf16_t* dq, bf16_t* dk,
+                    bf16_t* dv, float* delta, hipStream_t stream) {
+  if (int rc = check_shape(s)) return rc;
+  const int64_t rows = (int64_t)s.batch * s.length * s.heads;
+  const double pairs = s.causal ? 0.5 * s.length * (s.length + 1.0) : (double)s.length * s.length;
+  const double unit = 2.0 * s.batch * s.heads * pairs * kHeadDim;  // one contraction over visible pairs
+  const double act = (double)s.batch * s.length * s.heads * kRowBytes;
+  {
+    LaunchTimer timer("attn_delta_kernel", 0, 2.0 * act, stream);
+    attn_delta_kernel<<<(unsigned)ceil_div(rows, 16), 256, 0, stream>>>(ctx, dctx, delta, s.batch, s.length, s.heads);
+  }
+  if (int rc = launch_status("attn_delta_kernel")) return rc;
+  AttnArgs a = make_args(s);
+  a.q = q; a.k = k; a.v = v; a.dctx = dctx; a.lse_in = lse; a.delta_in = delta;
+  dim3 grid((unsigned)ceil_div(s.length, 64), (unsigned)s.heads, (unsigned)s.batch);
+  a.out0 = dq;
+  {  // dq = einsum(ds, k): 1 of the 4 backward contractions (dp and the recomputed logits are overhead here)
+    LaunchTimer timer("attn_dq_kernel<2>", unit, 5.0 * act, stream);
+    attn_dq_kernel<2><<<grid, 128, 0, stream>>>(a);
+  }
+  if (int rc = launch_status("attn_dq_kernel")) return rc;
+  a.out0 = dk;
+  a.out1 = dv;
+  {  // dp, dv, dk: 3 of the 4 backward contractions
+    LaunchTimer timer("attn_dkv_kernel<2>", 3.0 * unit, 6.0 * act, stream);
+    attn_dkv_kernel<2><<<grid, 128, 0, stream>>>(a);
+  }
+  return launch_status("attn_dkv_kernel");
+}
+
+}  // namespace mtf

@@ -4,6 +4,7 @@
 // other legal request runs on a generic fp32-FMA kernel (one thread per output element).
 #include "device_common.h"
 #include "gemm_bf16.h"
+#include "timing.h"
 
 namespace mtf {
 
@@ -116,6 +117,7 @@ int launch_generic(const void* a, const Dims& da, const void* b, const Dims* db,
   g.epi = epi;
   g.has_b = db ? 1 : 0;
   const int blocks = (int)std::min<int64_t>(ceil_div(g.out_elems, 256), 256 * 32);
+  LaunchTimer timer("einsum_generic_kernel", 2.0 * g.out_elems * g.red_points, 0, stream);
   if (in_dt == MTF_F32 && out_dt == MTF_F32)
     einsum_generic_kernel<float, float><<<blocks, 256, 0, stream>>>(
         (const float*)a, (const float*)b, (float*)out, (const float*)aux, g);

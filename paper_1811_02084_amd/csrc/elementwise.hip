@@ -1,5 +1,6 @@
 // HBM-bound helpers: slice gather/scatter, partial-sum reduce, dtype cast.
 #include "device_common.h"
+#include "timing.h"
 
 namespace mtf {
 
@@ -75,6 +76,7 @@ static int slice_copy_typed(const void* full, void* slice, const Dims& t, const 
   for (int d = 0; d + 1 < box.rank; ++d) vec_ok = vec_ok && box.stride[d] % kVec == 0;
   const ElemT* fc = static_cast<const ElemT*>(full);
   ElemT* fm = scatter ? const_cast<ElemT*>(fc) : nullptr;
+  LaunchTimer timer("slice_copy_kernel", 0, 2.0 * elems * sizeof(ElemT), stream);
   if (vec_ok) {
     box.extent[box.rank - 1] = inner / kVec;
     box.vectors = elems / kVec;
@@ -186,6 +188,8 @@ int mtf_reduce_partials(const void* const* partials, int32_t n, const void* resi
   hipStream_t s = static_cast<hipStream_t>(stream);
   int blocks = (int)std::min<int64_t>(ceil_div(ceil_div(count, 4), 256), 256 * 8);
   bool rb = residual && residual_dt == MTF_BF16, ob = out_dt == MTF_BF16;
+  LaunchTimer timer("reduce_partials_kernel", 0,
+                    (double)count * (4.0 * n + (residual ? (rb ? 2 : 4) : 0) + (ob ? 2 : 4)), s);
   if (rb && ob)
     reduce_partials_kernel<true, true><<<blocks, 256, 0, s>>>(pp, n, residual, out, count);
   else if (rb)
@@ -205,6 +209,7 @@ int mtf_cast(const void* in, mtf_dtype in_dt, void* out, mtf_dtype out_dt, int64
   hipStream_t s = static_cast<hipStream_t>(stream);
   int blocks = (int)std::min<int64_t>(ceil_div(count, 256), 256 * 8);
   bool ib = in_dt == MTF_BF16, ob = out_dt == MTF_BF16;
+  LaunchTimer timer("cast_kernel", 0, (double)count * ((ib ? 2 : 4) + (ob ? 2 : 4)), s);
   if (ib && ob)
     cast_kernel<true, true><<<blocks, 256, 0, s>>>(in, out, count);
   else if (ib)

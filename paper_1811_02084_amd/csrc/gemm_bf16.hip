@@ -19,6 +19,8 @@
 //     each XCD (own L2) work on a compact patch of C.
 #include "gemm_bf16.h"
 
+#include "timing.h"
+
 namespace mtf {
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
@@ -301,8 +303,23 @@ __global__ void __launch_bounds__(kThreads) gemm_bf16_kernel(GemmArgs g) {
 
 template <bool A_K, bool B_K, int EPI, bool OUT_BF16>
 int launch_instance(const GemmArgs& a, dim3 grid, hipStream_t stream) {
-  auto kernel = gemm_bf16_kernel<A_K, B_K, EPI, OUT_BF16>;
-  kernel<<<grid, kThreads, 0, stream>>>(a);
+  // name as a profiler prints the instantiation
+  static const char* const kName =
+      A_K ? (B_K ? (OUT_BF16 ? (EPI == 0 ? "gemm_bf16_kernel<true, true, 0, true>" : EPI == 1 ? "gemm_bf16_kernel<true, true, 1, true>" : "gemm_bf16_kernel<true, true, 2, true>")
+                             : (EPI == 0 ? "gemm_bf16_kernel<true, true, 0, false>" : EPI == 1 ? "gemm_bf16_kernel<true, true, 1, false>" : "gemm_bf16_kernel<true, true, 2, false>"))
+                 : (OUT_BF16 ? (EPI == 0 ? "gemm_bf16_kernel<true, false, 0, true>" : EPI == 1 ? "gemm_bf16_kernel<true, false, 1, true>" : "gemm_bf16_kernel<true, false, 2, true>")
+                             : (EPI == 0 ? "gemm_bf16_kernel<true, false, 0, false>" : EPI == 1 ? "gemm_bf16_kernel<true, false, 1, false>" : "gemm_bf16_kernel<true, false, 2, false>")))
+          : (B_K ? (OUT_BF16 ? (EPI == 0 ? "gemm_bf16_kernel<false, true, 0, true>" : EPI == 1 ? "gemm_bf16_kernel<false, true, 1, true>" : "gemm_bf16_kernel<false, true, 2, true>")
+                             : (EPI == 0 ? "gemm_bf16_kernel<false, true, 0, false>" : EPI == 1 ? "gemm_bf16_kernel<false, true, 1, false>" : "gemm_bf16_kernel<false, true, 2, false>"))
+                 : (OUT_BF16 ? (EPI == 0 ? "gemm_bf16_kernel<false, false, 0, true>" : EPI == 1 ? "gemm_bf16_kernel<false, false, 1, true>" : "gemm_bf16_kernel<false, false, 2, true>")
+                             : (EPI == 0 ? "gemm_bf16_kernel<false, false, 0, false>" : EPI == 1 ? "gemm_bf16_kernel<false, false, 1, false>" : "gemm_bf16_kernel<false, false, 2, false>")));
+  double ktot = 0;
+  for (int s = 0; s < a.nseg; ++s) ktot += a.K[s];
+  const double batch = grid.y;
+  const double flops = 2.0 * a.M * a.N * ktot * batch;
+  const double bytes = batch * (2.0 * ktot * (a.M + a.N) + (double)a.M * a.N * (OUT_BF16 ? 2 : 4));
+  LaunchTimer timer(kName, flops, bytes, stream);
+  gemm_bf16_kernel<A_K, B_K, EPI, OUT_BF16><<<grid, kThreads, 0, stream>>>(a);
   return launch_status("gemm_bf16_kernel");
 }
 

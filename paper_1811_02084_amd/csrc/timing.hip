@@ -1,0 +1,99 @@
+// Per-launch kernel timing: every launch made while timing is enabled is bracketed by a pair of
+// HIP events recorded on the launch's own stream; mtf_timing_collect() turns them into per-kernel
+// totals.  Used by the benchmark to time the dominant kernel inside the timed region.
+#include "timing.h"
+
+#include <cstring>
+#include <mutex>
+#include <vector>
+
+#include "device_common.h"
+
+namespace mtf {
+namespace {
+
+struct Record {
+  const char* kind;
+  double flops, bytes;
+  hipEvent_t start, stop;
+};
+
+std::mutex g_mu;
+bool g_enabled = false;
+std::vector<Record> g_records;
+std::vector<hipEvent_t> g_free_events;
+
+hipEvent_t take_event() {
+  if (!g_free_events.empty()) {
+    hipEvent_t e = g_free_events.back();
+    g_free_events.pop_back();
+    return e;
+  }
+  hipEvent_t e = nullptr;
+  if (hipEventCreate(&e) != hipSuccess) return nullptr;
+  return e;
+}
+
+}  // namespace
+
+LaunchTimer::LaunchTimer(const char* kind, double flops, double bytes, hipStream_t stream)
+    : slot_(-1), stream_(stream) {
+  std::lock_guard<std::mutex> lock(g_mu);
+  if (!g_enabled) return;
+  Record r{kind, flops, bytes, take_event(), take_event()};
+  if (!r.start || !r.stop) return;
+  (void)hipEventRecord(r.start, stream);
+  g_records.push_back(r);
+  slot_ = (int)g_records.size() - 1;
+}
+
+LaunchTimer::~LaunchTimer() {
+  if (slot_ < 0) return;
+  std::lock_guard<std::mutex> lock(g_mu);
+  if (slot_ < (int)g_records.size()) (void)hipEventRecord(g_records[slot_].stop, stream_);
+}
+
+}  // namespace mtf
+
+using namespace mtf;
+
+extern "C" {
+
+int mtf_timing_enable(int on) {
+  std::lock_guard<std::mutex> lock(g_mu);
+  g_enabled = on != 0;
+  return MTF_OK;
+}
+
+int mtf_timing_collect(mtf_kernel_time* out, int32_t max_kinds, int32_t* n_kinds) {
+  if (!n_kinds || (max_kinds > 0 && !out)) return fail(MTF_ERR_NULL, "out / n_kinds");
+  std::lock_guard<std::mutex> lock(g_mu);
+  int n = 0;
+  int rc = MTF_OK;
+  for (Record& r : g_records) {
+    float ms = 0.f;
+    hipError_t e = hipEventSynchronize(r.stop);
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, r.start, r.stop);
+    if (e != hipSuccess) rc = hip_fail(e, "timing event");
+    g_free_events.push_back(r.start);
+    g_free_events.push_back(r.stop);
+    if (e != hipSuccess) continue;
+    int k = 0;
+    while (k < n && std::strcmp(out[k].kernel, r.kind) != 0) ++k;
+    if (k == n) {
+      if (n >= max_kinds) continue;
+      std::memset(&out[n], 0, sizeof out[n]);
+      std::strncpy(out[n].kernel, r.kind, sizeof out[n].kernel - 1);
+      ++n;
+    }
+    out[k].launches += 1;
+    out[k].total_ms += ms;
+    out[k].flops += r.flops;
+    out[k].bytes += r.bytes;
+  }
+  g_records.clear();
+  *n_kinds = n;
+  return rc;
+}
+
+}  // extern "C"
