@@ -174,9 +174,11 @@ int mtf_slice_copy(const void* full, void* slice, const mtf_shape* t, const mtf_
 int mtf_reduce_partials(const void* const* partials, int32_t n, const void* residual,
                         mtf_dtype residual_dt, void* out, mtf_dtype out_dt, int64_t count,
                         void* stream) {
-  if (!partials || !out) return fail(MTF_ERR_NULL, "partials / out");
+  if (!partials) return fail(MTF_ERR_NULL, "partials");
   if (n < 1 || n > 64) return fail(MTF_ERR_UNSUPPORTED, "%d partials (1..64)", n);
   if (count < 0) return fail(MTF_ERR_SIZE_MISMATCH, "count %lld", (long long)count);
+  if (count == 0) return MTF_OK;  // nothing to sum: buffers may legitimately be empty (NULL)
+  if (!out) return fail(MTF_ERR_NULL, "out");
   PartialPtrs pp;
   for (int i = 0; i < n; ++i) {
     if (!partials[i]) return fail(MTF_ERR_NULL, "partial %d", i);
@@ -184,7 +186,6 @@ int mtf_reduce_partials(const void* const* partials, int32_t n, const void* resi
     pp.p[i] = static_cast<const float*>(partials[i]);
   }
   if (!aligned16(out) || !aligned16(residual)) return fail(MTF_ERR_ALIGN, "out / residual");
-  if (count == 0) return MTF_OK;
   hipStream_t s = static_cast<hipStream_t>(stream);
   int blocks = (int)std::min<int64_t>(ceil_div(ceil_div(count, 4), 256), 256 * 8);
   bool rb = residual && residual_dt == MTF_BF16, ob = out_dt == MTF_BF16;
@@ -203,9 +204,9 @@ int mtf_reduce_partials(const void* const* partials, int32_t n, const void* resi
 
 int mtf_cast(const void* in, mtf_dtype in_dt, void* out, mtf_dtype out_dt, int64_t count,
              void* stream) {
-  if (!in || !out) return fail(MTF_ERR_NULL, "in / out");
   if (count < 0) return fail(MTF_ERR_SIZE_MISMATCH, "count %lld", (long long)count);
   if (count == 0) return MTF_OK;
+  if (!in || !out) return fail(MTF_ERR_NULL, "in / out");
   hipStream_t s = static_cast<hipStream_t>(stream);
   int blocks = (int)std::min<int64_t>(ceil_div(count, 256), 256 * 8);
   bool ib = in_dt == MTF_BF16, ob = out_dt == MTF_BF16;

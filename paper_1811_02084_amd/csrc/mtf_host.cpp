@@ -46,6 +46,16 @@ struct Place {
   const int64_t* coord = nullptr;
 };
 
+static int check_coord(const mtf_place* p, Place* out) {
+  if (!p->coord) return fail(MTF_ERR_NULL, "coordinate");
+  for (int i = 0; i < out->mesh.rank; ++i)
+    if (p->coord[i] < 0 || p->coord[i] >= out->mesh.size[i])
+      return fail(MTF_ERR_COORD_RANGE, "coordinate %lld on mesh dim '%s' of size %lld",
+                  (long long)p->coord[i], out->mesh.name[i], (long long)out->mesh.size[i]);
+  out->coord = p->coord;
+  return MTF_OK;
+}
+
 static int load_place(const mtf_place* p, bool need_coord, Place* out) {
   if (!p) return fail(MTF_ERR_NULL, "place");
   if (int rc = load_shape(&p->mesh, "mesh", &out->mesh)) return rc;
@@ -63,14 +73,7 @@ static int load_place(const mtf_place* p, bool need_coord, Place* out) {
     if (out->rule_axis[i] < 0)
       return fail(MTF_ERR_UNKNOWN_MESH_DIM, "'%s' -> '%s'", r.tensor_dim, r.mesh_dim);
   }
-  if (need_coord) {
-    if (!p->coord) return fail(MTF_ERR_NULL, "coordinate");
-    for (int i = 0; i < out->mesh.rank; ++i)
-      if (p->coord[i] < 0 || p->coord[i] >= out->mesh.size[i])
-        return fail(MTF_ERR_COORD_RANGE, "coordinate %lld on mesh dim '%s' of size %lld",
-                    (long long)p->coord[i], out->mesh.name[i], (long long)out->mesh.size[i]);
-    out->coord = p->coord;
-  }
+  if (need_coord) return check_coord(p, out);
   return MTF_OK;
 }
 
@@ -109,11 +112,14 @@ static int stripes(const Dims& t, const Place& pl, const int* axis, int64_t* off
   return MTF_OK;
 }
 
+// Order of checks (first failure wins): mesh and rules, injectivity of the tensor's layout,
+// coordinate range, divisibility.
 int slice_of(const Dims& t, const mtf_place* p, int64_t* offset, int64_t* size) {
   Place pl;
-  if (int rc = load_place(p, true, &pl)) return rc;
+  if (int rc = load_place(p, false, &pl)) return rc;
   int axis[MTF_MAX_RANK];
   if (int rc = restrict_layout(t, pl, axis)) return rc;
+  if (int rc = check_coord(p, &pl)) return rc;
   return stripes(t, pl, axis, offset, size);
 }
 
@@ -266,8 +272,6 @@ int mtf_einsum_plan(const mtf_shape* a, const mtf_shape* b, const mtf_shape* out
   if (b)
     if (int rc = load_shape(b, "b", &db)) return rc;
   if (int rc = load_shape(out, "output", &dout)) return rc;
-  Place pl;
-  if (int rc = load_place(p, false, &pl)) return rc;
   // union of the operands' dims (may exceed MTF_MAX_RANK, so keep a wider table)
   const char* uname[2 * MTF_MAX_RANK];
   int64_t usize[2 * MTF_MAX_RANK];
@@ -295,6 +299,8 @@ int mtf_einsum_plan(const mtf_shape* a, const mtf_shape* b, const mtf_shape* out
       return fail(MTF_ERR_SIZE_MISMATCH, "output dim '%s' is %lld, inputs have %lld", dout.name[i],
                   (long long)dout.size[i], (long long)usize[j]);
   }
+  Place pl;
+  if (int rc = load_place(p, false, &pl)) return rc;
   // layout restricted to the union: injective over the whole einsum
   int uaxis[2 * MTF_MAX_RANK], owner[MTF_MAX_RANK];
   for (int i = 0; i < un; ++i) uaxis[i] = -1;

@@ -1,0 +1,130 @@
+"""GPU parity tests of mtf_einsum_local against the oracle's named einsum: the MFMA GEMM in
+all operand layouts (with ragged edges, batches, epilogues) and the generic fp32 kernel."""
+import numpy as np
+import pytest
+import torch
+
+import paper_1811_02084_amd as mtf
+from oracle.bf16 import round_to_bf16
+from oracle.einsum import NT, einsum, einsum_abs
+from oracle.metrics import m1, m2
+from helpers import f64, named, BF16_TOL, F32_TOL
+
+pytestmark = pytest.mark.gpu
+
+SIZES = dict(m=304, n=264, k=200, b=3, h=2, p=5)      # several tiles and ragged tails (tile 256, k 64)
+
+
+def _rand(dims, dtype, seed, sizes=SIZES, ints=False):
+    rng = np.random.default_rng(seed)
+    shape = [sizes[d] for d in dims]
+    a = rng.integers(-2, 3, shape).astype(np.float32) if ints else rng.standard_normal(shape).astype(np.float32)
+    return torch.from_numpy(a).to(dtype)
+
+
+GEMM_CASES = [
+    ("nn", "mk", "kn", "mn"), ("nt", "mk", "nk", "mn"), ("tn", "km", "kn", "mn"), ("tt", "km", "nk", "mn"),
+    ("out transposed", "mk", "kn", "nm"), ("batched", "bmk", "bkn", "bmn"),
+    ("two batch dims, strided rows", "bmhk", "bnhk", "bhmn"),
+    ("k folded from two dims", "mhk", "hkn", "mn"), ("vector out", "k", "kn", "n"),
+]
+
+
+@pytest.mark.parametrize("name,da,db,do", GEMM_CASES)
+def test_bf16_contractions(name, da, db, do):
+    print(f"einsum_local bf16 {name}: {da},{db}->{do}", flush=True)
+    a, b = _rand(da, torch.bfloat16, 1), _rand(db, torch.bfloat16, 2)
+    got = mtf.einsum_local(a.cuda(), da, b.cuda(), db, do, out_dtype=torch.float32)
+    ins = [named(a, da), named(b, db)]
+    ref, ref_abs = einsum(ins, do), einsum_abs(ins, do)
+    assert m1(f64(got), ref.data, ref_abs.data) <= 1e-5      # fp32 accumulation of exact products
+    assert m2(f64(got), ref.data) <= BF16_TOL
+    got16 = mtf.einsum_local(a.cuda(), da, b.cuda(), db, do, out_dtype=torch.bfloat16)
+    assert m2(f64(got16), round_to_bf16(ref.data)) <= BF16_TOL
+
+
+@pytest.mark.parametrize("name,da,db,do", GEMM_CASES[:4])
+def test_bf16_integer_inputs_are_exact(name, da, db, do):
+    """Small integers: every product and partial sum is exact in fp32, whatever the order."""
+    print(f"einsum_local exact ints {name}", flush=True)
+    a, b = _rand(da, torch.bfloat16, 3, ints=True), _rand(db, torch.bfloat16, 4, ints=True)
+    got = mtf.einsum_local(a.cuda(), da, b.cuda(), db, do, out_dtype=torch.float32)
+    ref = einsum([named(a, da), named(b, db)], do)
+    assert np.array_equal(f64(got), ref.data)
+
+
+def test_epilogues_alpha_accumulate():
+    da, db, do = "mk", "kn", "mn"
+    a, b = _rand(da, torch.bfloat16, 5), _rand(db, torch.bfloat16, 6)
+    ref = einsum([named(a, da), named(b, db)], do).data
+    print("relu", flush=True)
+    got = mtf.einsum_local(a.cuda(), da, b.cuda(), db, do, out_dtype=torch.bfloat16, epi=mtf.EPI_RELU)
+    assert m2(f64(got), round_to_bf16(np.maximum(ref, 0))) <= BF16_TOL
+    assert float(got.float().min()) >= 0.0
+    print("mask", flush=True)
+    aux = _rand(do, torch.bfloat16, 7)
+    aux[0, :8] = 0.0                                          # exactly zero: masked (gradient 0 at 0)
+    got = mtf.einsum_local(a.cuda(), da, b.cuda(), db, do, out_dtype=torch.float32, epi=mtf.EPI_MASK_GT0,
+                           aux=aux.cuda())
+    assert m2(f64(got), np.where(f64(aux) > 0, ref, 0.0)) <= BF16_TOL
+    assert np.all(f64(got)[f64(aux) <= 0] == 0.0)
+    print("alpha + accumulate", flush=True)
+    init = _rand(do, torch.float32, 8)
+    out = init.clone().cuda()
+    mtf.einsum_local(a.cuda(), da, b.cuda(), db, do, alpha=0.25, accumulate=True, out=out)
+    assert m2(f64(out), 0.25 * ref + f64(init)) <= BF16_TOL
+
+
+@pytest.mark.parametrize("sizes", [dict(m=8, n=8, k=8), dict(m=1, n=8, k=16), dict(m=257, n=8, k=8),
+                                   dict(m=64, n=512, k=72), dict(m=512, n=256, k=1024)])
+def test_edge_sizes(sizes):
+    print(f"einsum_local sizes {sizes}", flush=True)
+    for da, db in (("mk", "kn"), ("mk", "nk"), ("km", "kn")):
+        if da == "km" and sizes["m"] % 8:
+            continue                                         # goes to the generic kernel; covered below
+        a, b = _rand(da, torch.bfloat16, 9, sizes), _rand(db, torch.bfloat16, 10, sizes)
+        got = mtf.einsum_local(a.cuda(), da, b.cuda(), db, "mn", out_dtype=torch.float32)
+        ins = [named(a, da), named(b, db)]
+        assert m1(f64(got), einsum(ins, "mn").data, einsum_abs(ins, "mn").data) <= 1e-5
+
+
+GENERIC_CASES = [
+    ("fp32 matmul", "bld", "df", "blf", torch.float32),
+    ("fp32 outer + reduce", "bm", "pn", "mn", torch.float32),
+    ("bf16 odd sizes", "mp", "pn", "mn", torch.bfloat16),
+    ("bf16 batch innermost", "bmk", "bkn", "mnb", torch.bfloat16),
+    ("scalar out", "mk", "mk", "", torch.float32),
+]
+
+
+@pytest.mark.parametrize("name,da,db,do,dtype", GENERIC_CASES)
+def test_generic_kernel(name, da, db, do, dtype):
+    print(f"einsum_local generic {name}", flush=True)
+    sizes = dict(b=2, l=8, d=16, f=64, m=33, n=18, k=70, p=5)
+    a, b = _rand(da, dtype, 11, sizes), _rand(db, dtype, 12, sizes)
+    got = mtf.einsum_local(a.cuda(), da, b.cuda(), db, do, out_dtype=torch.float32)
+    ins = [named(a, da), named(b, db)]
+    ref, ref_abs = einsum(ins, do), einsum_abs(ins, do)
+    assert tuple(got.shape) == ref.data.shape
+    assert m1(f64(got), ref.data, ref_abs.data) <= F32_TOL
+
+
+def test_one_operand_einsum_and_errors():
+    a = _rand("bmk", torch.float32, 13, dict(b=3, m=4, k=5))
+    got = mtf.einsum_local(a.cuda(), "bmk", None, None, "kb")           # reduce + transpose
+    assert m2(f64(got), f64(a).sum(axis=1).T) <= F32_TOL
+    with pytest.raises(mtf.MtfError) as e:
+        mtf.einsum_local(a.cuda(), "bmk", None, None, "bq")
+    assert e.value.name == "MTF_ERR_OUT_NOT_SUBSET"
+    with pytest.raises(mtf.MtfError) as e:
+        mtf.einsum_local(a.cuda(), "bmk", a.cuda()[:, :, :4].contiguous(), "bmk", "bm")
+    assert e.value.name == "MTF_ERR_SIZE_MISMATCH"
+    with pytest.raises(mtf.MtfError) as e:
+        mtf.einsum_local(a.cuda(), "bmm", None, None, "b")
+    assert e.value.name == "MTF_ERR_DUP_DIM"
+
+
+def test_run_to_run_bitwise_determinism():
+    a, b = _rand("mk", torch.bfloat16, 14), _rand("kn", torch.bfloat16, 15)
+    outs = [mtf.einsum_local(a.cuda(), "mk", b.cuda(), "kn", "mn", out_dtype=torch.float32).cpu() for _ in range(3)]
+    assert torch.equal(outs[0], outs[1]) and torch.equal(outs[0], outs[2])

@@ -1,0 +1,109 @@
+"""The paper's central invariant on the device: every layout gives the identical result.
+A virtual mesh of slices is held on one GPU; each coordinate's slices are gathered with
+mtf_slice_copy, its share of the layer is computed, and the partial sums are reduced along the
+mesh dims the einsum plan names (the stand-in for the Allreduce)."""
+import numpy as np
+import pytest
+import torch
+
+import mtf_inputs
+import paper_1811_02084_amd as mtf
+from oracle import layer as OL
+from oracle import layout as OLY
+from oracle.einsum import NT
+from oracle.metrics import m2
+from helpers import f64, named, on_device, BF16_TOL, F32_TOL
+from oracle.layer import B, L, D, F
+
+pytestmark = pytest.mark.gpu
+
+X, WI, WO, HID = (B, L, D), (D, F), (F, D), (B, L, F)
+
+
+def _virtual_mesh_ffn(g, mesh, layout, fp32):
+    """Returns {coord: y after the grouped reduce} computed slice by slice on the device."""
+    shp = lambda t, dims: list(zip(dims, t.shape))
+    plan = mtf.einsum_plan(shp(g["x"], X)[:2] + [(F, g["w_in"].shape[1])], shp(g["w_out"], WO),
+                           shp(g["x"], X), mesh, layout)
+    axes = plan["reduce_axes"]
+    partial = {}
+    for c in OLY.all_coords(mesh):
+        xs = mtf.slice_copy(g["x"], X, mesh, layout, c)
+        wi = mtf.slice_copy(g["w_in"], WI, mesh, layout, c)
+        wo = mtf.slice_copy(g["w_out"], WO, mesh, layout, c)
+        if fp32:
+            h = mtf.einsum_local(xs, X, wi, WI, HID, epi=mtf.EPI_RELU)
+            partial[c] = mtf.einsum_local(h, HID, wo, WO, X)
+        else:
+            partial[c] = mtf.ffn_fwd(xs, wi, wo)[1]
+    out = {}
+    for c in OLY.all_coords(mesh):
+        group = [c2 for c2 in OLY.all_coords(mesh)
+                 if all(c2[i] == c[i] for i in range(len(mesh)) if i not in axes)]
+        out[c] = mtf.reduce_partials([partial[c2] for c2 in group])
+    return out, axes
+
+
+def test_config1_tiny_fp32_mesh_of_4():
+    cfg = mtf_inputs.config1()
+    g = on_device(cfg)
+    mesh, layout = cfg["mesh"], cfg["layout"]
+    out, axes = _virtual_mesh_ffn(g, mesh, layout, fp32=True)
+    assert axes == [0]                                        # d_ff is reduced out and split
+    ref = OL.ffn_fwd(named(cfg["x"], X), named(cfg["w_in"], WI), named(cfg["w_out"], WO), OL.identity)["y"]
+    for c, y in out.items():
+        assert m2(f64(y), ref.data) <= F32_TOL, c             # every processor ends with the full y
+    # unsplit computation on the device agrees as well
+    h = mtf.einsum_local(g["x"], X, g["w_in"], WI, HID, epi=mtf.EPI_RELU)
+    y = mtf.einsum_local(h, HID, g["w_out"], WO, X)
+    assert m2(f64(y), ref.data) <= F32_TOL
+
+
+@pytest.mark.parametrize("mesh,layout", [
+    ([("all", 4)], [("batch", "all")]),
+    ([("all", 4)], [("d_ff", "all")]),
+    ([("rows", 2), ("cols", 2)], [("batch", "rows"), ("d_ff", "cols")]),
+    ([("rows", 2), ("cols", 2), ("planes", 2)], [("batch", "rows"), ("d_ff", "cols"), ("d_model", "planes")]),
+    ([("all", 3)], []),
+])
+def test_layouts_of_the_worked_example_bit_exact_on_integers(mesh, layout):
+    """Integer-valued inputs: all partial sums are exact, so every layout must agree bit for bit."""
+    print(f"layout {layout} on {mesh}", flush=True)
+    x = mtf_inputs.small_ints(31, 0, (4, 6, 16), dtype=torch.float32).cuda()
+    w_in = mtf_inputs.small_ints(31, 1, (16, 24), dtype=torch.float32).cuda()
+    hidden_full = mtf.einsum_local(x, X, w_in, WI, HID)
+    for c in OLY.all_coords(mesh):
+        plan = mtf.einsum_plan(list(zip(X, x.shape)), list(zip(WI, w_in.shape)),
+                               list(zip(HID, hidden_full.shape)), mesh, layout)
+        group = [c2 for c2 in OLY.all_coords(mesh)
+                 if all(c2[i] == c[i] for i in range(len(mesh)) if i not in plan["reduce_axes"])]
+        parts = [mtf.einsum_local(mtf.slice_copy(x, X, mesh, layout, c2), X,
+                                  mtf.slice_copy(w_in, WI, mesh, layout, c2), WI, HID) for c2 in group]
+        got = mtf.reduce_partials(parts)
+        want = mtf.slice_copy(hidden_full, HID, mesh, layout, c)
+        assert torch.equal(got, want), c
+
+
+def test_config4_virtual_4x4_mesh_full_size():
+    cfg = mtf_inputs.config4()
+    g = on_device(cfg)
+    mesh, layout = cfg["mesh"], cfg["layout"]
+    print("config 4: 16 slices", flush=True)
+    out, axes = _virtual_mesh_ffn(g, mesh, layout, fp32=False)
+    assert axes == [1]                                        # summed by processor-column index
+    print("config 4: unsplit layer on the device", flush=True)
+    _, y_full = mtf.ffn_fwd(g["x"], g["w_in"], g["w_out"])
+    for c, y in out.items():
+        want = mtf.slice_copy(y_full, X, mesh, layout, c)
+        # identical bf16 products, fp32 sums taken in a different order
+        assert m2(f64(y), f64(want)) <= 1e-4, c
+    # against the oracle on sampled tokens (a feed-forward output row depends on its own input row only)
+    print("config 4: oracle on sampled tokens", flush=True)
+    rng = np.random.default_rng(4)
+    w_in, w_out = named(cfg["w_in"], WI), named(cfg["w_out"], WO)
+    for bi, li in zip(rng.integers(0, 64, 12), rng.integers(0, 256, 12)):
+        xr = NT(f64(cfg["x"][bi:bi + 1, li:li + 1]), X)
+        ref = OL.ffn_fwd(xr, w_in, w_out)["y"].data[0, 0]
+        r = bi // 16
+        got = f64(out[(r, 0)])[bi - 16 * r, li]
+        assert m2(got, ref) <= BF16_TOL, (bi, li)

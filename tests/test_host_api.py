@@ -1,0 +1,144 @@
+"""CPU-only tests of the C-ABI library: it loads, exports every declared symbol, and its
+host-side integer logic (mesh numbering, slices, einsum lowering plan, error codes) agrees
+bit-for-bit with the oracle.  No kernel is launched here."""
+import ctypes as C
+import os
+import random
+import re
+
+import pytest
+
+import paper_1811_02084_amd as mtf
+from oracle import layout as OLY
+from oracle.einsum import EinsumError
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_every_declared_symbol_is_exported():
+    header = open(os.path.join(ROOT, "include", "mtf.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(mtf_[a-z0-9_]+)\s*\(", header))
+    assert len(declared) >= 20
+    for name in sorted(declared):
+        assert hasattr(mtf.lib, name), f"{name} declared in mtf.h but not exported by libmtf.so"
+
+
+def test_status_strings():
+    for code, name in mtf.STATUS.items():
+        assert mtf.status_string(code) == name
+
+
+def _code(exc):
+    """Oracle error code -> library status name."""
+    return "MTF_ERR_" + exc.code
+
+
+def _random_case(rnd):
+    mesh_names = ["rows", "cols", "planes", "all"]
+    mesh = [(n, rnd.choice([1, 2, 3, 4])) for n in rnd.sample(mesh_names, rnd.randint(1, 3))]
+    tdims = ["batch", "length", "d_model", "d_ff", "heads", "d_k", "vocab"]
+    dims = rnd.sample(tdims, rnd.randint(0, 5))
+    shape = [(d, rnd.choice([1, 2, 3, 4, 6, 8, 12, 24])) for d in dims]
+    layout = []
+    for d in rnd.sample(tdims, rnd.randint(0, 4)):
+        layout.append((d, rnd.choice([m for m, _ in mesh] + (["nowhere"] if rnd.random() < 0.05 else []))))
+    if layout and rnd.random() < 0.05:
+        layout.append(layout[0])                       # duplicate rule
+    coord = [rnd.randrange(s) for _, s in mesh]
+    if rnd.random() < 0.05:
+        coord[0] = mesh[0][1]                          # out of range
+    return mesh, shape, layout, coord
+
+
+def test_slice_matches_oracle_on_random_cases():
+    rnd = random.Random(1811)
+    n_ok = n_err = 0
+    for _ in range(3000):
+        mesh, shape, layout, coord = _random_case(rnd)
+        dims, sizes = [d for d, _ in shape], [s for _, s in shape]
+        try:
+            want = OLY.slice_spec(dims, sizes, mesh, layout, tuple(coord))
+        except OLY.LayoutError as e:
+            with pytest.raises(mtf.MtfError) as got:
+                mtf.slice(shape, mesh, layout, coord)
+            assert got.value.name == _code(e), (mesh, shape, layout, coord)
+            n_err += 1
+            continue
+        assert mtf.slice(shape, mesh, layout, coord) == want, (mesh, shape, layout, coord)
+        n_ok += 1
+    assert n_ok > 500 and n_err > 200
+
+
+def test_rank_coord_round_trip_and_three_views():
+    for mesh in ([("a", 16), ("b", 16), ("c", 2)], [("a", 32), ("b", 16)], [("a", 512)]):
+        for rank in (0, 1, 31, 37, 255, 511):
+            c = mtf.rank_to_coord(mesh, rank)
+            assert c == OLY.rank_to_coord(mesh, rank)
+            assert mtf.coord_to_rank(mesh, c) == rank
+        with pytest.raises(mtf.MtfError) as e:
+            mtf.rank_to_coord(mesh, 512)
+        assert e.value.name == "MTF_ERR_COORD_RANGE"
+    with pytest.raises(mtf.MtfError):
+        mtf.coord_to_rank([("a", 4)], (4,))
+
+
+def test_einsum_plan_matches_oracle():
+    rnd = random.Random(2084)
+    tdims = ["batch", "length", "d_model", "d_ff", "heads", "d_k"]
+    n_ok = n_err = 0
+    for _ in range(2000):
+        mesh, _, layout, _ = _random_case(rnd)
+        size = {d: rnd.choice([2, 4, 6, 8, 12]) for d in tdims}
+        da, db = rnd.sample(tdims, rnd.randint(1, 4)), rnd.sample(tdims, rnd.randint(1, 4))
+        pool = list(dict.fromkeys(da + db))
+        do = rnd.sample(pool, rnd.randint(0, len(pool)))
+        if rnd.random() < 0.05:
+            do = do + ["vocab"]
+        a, b = [(d, size[d]) for d in da], [(d, size[d]) for d in db]
+        o = [(d, size.get(d, 3)) for d in do]
+        try:
+            want = OLY.einsum_plan([da, db], [[s for _, s in a], [s for _, s in b]], do, mesh, layout)
+        except (OLY.LayoutError, EinsumError) as e:
+            with pytest.raises(mtf.MtfError) as got:
+                mtf.einsum_plan(a, b, o, mesh, layout)
+            assert got.value.name == _code(e), (a, b, o, mesh, layout)
+            n_err += 1
+            continue
+        got = mtf.einsum_plan(a, b, o, mesh, layout)
+        assert got["local_in"] == want["local_in"] and got["local_out"] == want["local_out"]
+        assert got["reduce_axes"] == want["reduce_axes"] and got["flops_local"] == want["flops_local"]
+        n_ok += 1
+    assert n_ok > 300 and n_err > 100
+
+
+def test_paper_layouts_through_the_library():
+    b, d_io, d_h, n = 48, 12, 24, 4
+    assert mtf.slice([("batch", b), ("io", d_io)], [("all", n)], [("batch", "all")], (3,)) == ((36, 0), (12, 12))
+    assert mtf.slice([("io", d_io), ("hidden", d_h)], [("all", n)], [("hidden", "all")], (1,)) == ((0, 6), (12, 6))
+    with pytest.raises(mtf.MtfError) as e:      # the illegal layout of the worked example
+        mtf.slice([("batch", b), ("hidden", d_h)], [("all", n)], [("batch", "all"), ("hidden", "all")], (0,))
+    assert e.value.name == "MTF_ERR_LAYOUT_CONFLICT"
+    plan = mtf.einsum_plan([("batch", b), ("hidden", d_h)], [("hidden", d_h), ("io", d_io)],
+                           [("batch", b), ("io", d_io)], [("rows", 2), ("cols", 2)],
+                           [("batch", "rows"), ("hidden", "cols")])
+    assert plan["reduce_axes"] == [1] and plan["local_out"] == (24, 12)     # summed by processor-column
+
+
+def test_argument_validation_needs_no_gpu():
+    """Entry points reject bad arguments before touching the device."""
+    lib = mtf.lib
+    d = mtf.mtf_ffn_dims(2, 8, 16, 64)
+    assert lib.mtf_ffn_fwd(C.byref(d), None, None, None, None, None, None) == -1          # NULL
+    bad = mtf.mtf_ffn_dims(2, 8, 15, 64)
+    p = C.c_void_p(4096)
+    assert lib.mtf_ffn_fwd(C.byref(bad), p, p, p, p, p, None) == -10                      # UNSUPPORTED
+    assert lib.mtf_ffn_bwd(C.byref(d), p, p, p, p, p, p, p, p, None, C.c_size_t(0), None) == -11   # WORKSPACE
+    m = mtf.mtf_mha_dims(2, 8, 16, 2, 64)
+    assert lib.mtf_mha_fwd(C.byref(m), p, p, p, p, p, C.c_float(1.0), 0, p, p, p, p, p, p, None) == -10
+    assert lib.mtf_ffn_fwd(C.byref(d), C.c_void_p(4097), p, p, p, p, None) == -14         # ALIGN
+    assert lib.mtf_ffn_bwd_workspace_bytes(C.byref(d)) == 2 * 8 * 64 * 2
+    assert lib.mtf_reduce_partials(None, 1, None, 0, p, 0, C.c_int64(4), None) == -1
+    arr = (C.c_void_p * 1)(None)
+    assert lib.mtf_reduce_partials(arr, 1, None, 0, None, 0, C.c_int64(0), None) == 0        # empty: nothing to do
+    assert b"MTF_ERR" in lib.mtf_last_error()
