@@ -161,14 +161,16 @@ __device__ __forceinline__ void store_rows_bf16(bf16_t* base, int64_t row_stride
 // ------------------------------------------------------------------------------------ forward
 // One workgroup: NWAVES*32 query rows of one (batch, head); each wave owns 32 of them.
 template <int NWAVES>
-__global__ void __launch_bounds__(NWAVES * 64) attn_fwd_kernel(AttnArgs a) {
-  __shared__ __attribute__((aligned(1024))) char k_tile[kTileBytes];
-  __shared__ __attribute__((aligned(1024))) char v_tile[kTileBytes];
+// second launch-bound argument: wavefronts per SIMD the register budget must allow
+__global__ void __launch_bounds__(NWAVES * 64, 2) attn_fwd_kernel(AttnArgs a) {
+  __shared__ __attribute__((aligned(1024))) char stage0[2 * kTileBytes];  // K tile, V tile
+  __shared__ __attribute__((aligned(1024))) char stage1[2 * kTileBytes];
   const int lane = threadIdx.x & 63, hf = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int L = a.length, H = a.heads;
   const int b = blockIdx.z, h = blockIdx.y;
-  const int q0 = blockIdx.x * (NWAVES * 32);
+  // causal: later query blocks see more memory positions; start those first
+  const int q0 = (a.causal ? gridDim.x - 1 - blockIdx.x : blockIdx.x) * (NWAVES * 32);
   const int64_t rs = (int64_t)H * kHeadDim;
   const int64_t head0 = ((int64_t)b * L) * rs + (int64_t)h * kHeadDim;
   const bf16_t *qb = a.q + head0, *kb = a.k + head0, *vb = a.v + head0;
@@ -186,13 +188,15 @@ __global__ void __launch_bounds__(NWAVES * 64) attn_fwd_kernel(AttnArgs a) {
   const float c2 = a.scale * kLog2e;
 
   const int kv_end = a.causal ? min(L, q0 + NWAVES * 32) : L;
-  for (int kv0 = 0; kv0 < kv_end; kv0 += kTileRows) {
-    __syncthreads();  // everyone is done with the previous tiles
-    load_tile<NWAVES>(kb, (uint32_t)(rs * 2), kv0, L, k_tile, wave, lane);
-    load_tile<NWAVES>(vb, (uint32_t)(rs * 2), kv0, L, v_tile, wave, lane);
-    wait_loads_then_barrier();
-    if (a.causal && kv0 > q0 + wave * 32 + 31) continue;  // nothing visible for this wave
-
+  const int n_tiles = (kv_end + kTileRows - 1) / kTileRows;
+  auto issue = [&](int t, char* st) {
+    load_tile<NWAVES>(kb, (uint32_t)(rs * 2), t * kTileRows, L, st, wave, lane);
+    load_tile<NWAVES>(vb, (uint32_t)(rs * 2), t * kTileRows, L, st + kTileBytes, wave, lane);
+  };
+  auto process = [&](int t, const char* st) {
+    const int kv0 = t * kTileRows;
+    const char *kt_ = st, *vt_ = st + kTileBytes;
+    if (a.causal && kv0 > q0 + wave * 32 + 31) return;  // nothing visible for this wave
     // logits^T: rows = memory positions of the tile, column = this lane's query
     f32x16 s[2];
 #pragma unroll
@@ -200,7 +204,7 @@ __global__ void __launch_bounds__(NWAVES * 64) attn_fwd_kernel(AttnArgs a) {
       s[kvb] = zero16();
 #pragma unroll
       for (int ks = 0; ks < 8; ++ks)
-        s[kvb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rows_frag(k_tile, kvb * 32, ks, lane), qf[ks],
+        s[kvb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rows_frag(kt_, kvb * 32, ks, lane), qf[ks],
                                                          s[kvb], 0, 0, 0);
     }
     float mx = -INFINITY;
@@ -239,9 +243,21 @@ __global__ void __launch_bounds__(NWAVES * 64) attn_fwd_kernel(AttnArgs a) {
       for (int e = 0; e < 16; ++e) o[blk][e] *= alpha;
 #pragma unroll
       for (int t = 0; t < 4; ++t)
-        o[blk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cols_frag(v_tile, blk * 32, t * 16, lane), pf[t],
+        o[blk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cols_frag(vt_, blk * 32, t * 16, lane), pf[t],
                                                          o[blk], 0, 0, 0);
     }
+  };
+  // Two stages: the tile after the one being processed is in flight.  Passing the barrier means
+  // everyone has the current tile and is done with the stage the next issue() overwrites.
+  issue(0, stage0);
+  for (int t = 0; t < n_tiles; t += 2) {
+    wait_loads_then_barrier();
+    if (t + 1 < n_tiles) issue(t + 1, stage1);
+    process(t, stage0);
+    if (t + 1 >= n_tiles) break;
+    wait_loads_then_barrier();
+    if (t + 2 < n_tiles) issue(t + 2, stage0);
+    process(t + 1, stage1);
   }
   store_rows_bf16(a.out0 + head0, rs, q_lane, L, o, 1.f / lsum, lane);
   if (q_lane < L && hf == 0)
@@ -278,14 +294,15 @@ __global__ void __launch_bounds__(256) attn_delta_kernel(const bf16_t* __restric
 
 // dq: one workgroup per NWAVES*32 query rows; loops over memory tiles.
 template <int NWAVES>
-__global__ void __launch_bounds__(NWAVES * 64) attn_dq_kernel(AttnArgs a) {
-  __shared__ __attribute__((aligned(1024))) char k_tile[kTileBytes];
-  __shared__ __attribute__((aligned(1024))) char v_tile[kTileBytes];
+__global__ void __launch_bounds__(NWAVES * 64, 2) attn_dq_kernel(AttnArgs a) {
+  __shared__ __attribute__((aligned(1024))) char stage0[2 * kTileBytes];  // K tile, V tile
+  __shared__ __attribute__((aligned(1024))) char stage1[2 * kTileBytes];
   const int lane = threadIdx.x & 63, hf = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int L = a.length, H = a.heads;
   const int b = blockIdx.z, h = blockIdx.y;
-  const int q0 = blockIdx.x * (NWAVES * 32);
+  // causal: later query blocks see more memory positions; start those first
+  const int q0 = (a.causal ? gridDim.x - 1 - blockIdx.x : blockIdx.x) * (NWAVES * 32);
   const int64_t rs = (int64_t)H * kHeadDim;
   const int64_t head0 = ((int64_t)b * L) * rs + (int64_t)h * kHeadDim;
   const bf16_t *qb = a.q + head0, *kb = a.k + head0, *vb = a.v + head0, *dob = a.dctx + head0;
@@ -307,21 +324,23 @@ __global__ void __launch_bounds__(NWAVES * 64) attn_dq_kernel(AttnArgs a) {
   for (int i = 0; i < 4; ++i) dq[i] = zero16();
 
   const int kv_end = a.causal ? min(L, q0 + NWAVES * 32) : L;
-  for (int kv0 = 0; kv0 < kv_end; kv0 += kTileRows) {
-    __syncthreads();
-    load_tile<NWAVES>(kb, (uint32_t)(rs * 2), kv0, L, k_tile, wave, lane);
-    load_tile<NWAVES>(vb, (uint32_t)(rs * 2), kv0, L, v_tile, wave, lane);
-    wait_loads_then_barrier();
-    if (a.causal && kv0 > q0 + wave * 32 + 31) continue;
-
+  const int n_tiles = (kv_end + kTileRows - 1) / kTileRows;
+  auto issue = [&](int t, char* st) {
+    load_tile<NWAVES>(kb, (uint32_t)(rs * 2), t * kTileRows, L, st, wave, lane);
+    load_tile<NWAVES>(vb, (uint32_t)(rs * 2), t * kTileRows, L, st + kTileBytes, wave, lane);
+  };
+  auto process = [&](int t, const char* st) {
+    const int kv0 = t * kTileRows;
+    const char *kt_ = st, *vt_ = st + kTileBytes;
+    if (a.causal && kv0 > q0 + wave * 32 + 31) return;
     bf16x8 dsf[4];
 #pragma unroll
     for (int kvb = 0; kvb < 2; ++kvb) {
       f32x16 s = zero16(), dp = zero16();
 #pragma unroll
       for (int ks = 0; ks < 8; ++ks) {
-        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rows_frag(k_tile, kvb * 32, ks, lane), qf[ks], s, 0, 0, 0);
-        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rows_frag(v_tile, kvb * 32, ks, lane), dof[ks], dp, 0, 0, 0);
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rows_frag(kt_, kvb * 32, ks, lane), qf[ks], s, 0, 0, 0);
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rows_frag(vt_, kvb * 32, ks, lane), dof[ks], dp, 0, 0, 0);
       }
       float ds[16];
 #pragma unroll
@@ -338,19 +357,29 @@ __global__ void __launch_bounds__(NWAVES * 64) attn_dq_kernel(AttnArgs a) {
     for (int blk = 0; blk < 4; ++blk)
 #pragma unroll
       for (int t = 0; t < 4; ++t)
-        dq[blk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cols_frag(k_tile, blk * 32, t * 16, lane), dsf[t],
+        dq[blk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cols_frag(kt_, blk * 32, t * 16, lane), dsf[t],
                                                           dq[blk], 0, 0, 0);
+  };
+  issue(0, stage0);
+  for (int t = 0; t < n_tiles; t += 2) {
+    wait_loads_then_barrier();
+    if (t + 1 < n_tiles) issue(t + 1, stage1);
+    process(t, stage0);
+    if (t + 1 >= n_tiles) break;
+    wait_loads_then_barrier();
+    if (t + 2 < n_tiles) issue(t + 2, stage0);
+    process(t + 1, stage1);
   }
   store_rows_bf16(a.out0 + head0, rs, q_lane, L, dq, 1.f, lane);
 }
 
 // dk, dv: one workgroup per NWAVES*32 memory rows; loops over query tiles.
 template <int NWAVES>
-__global__ void __launch_bounds__(NWAVES * 64) attn_dkv_kernel(AttnArgs a) {
-  __shared__ __attribute__((aligned(1024))) char q_tile[kTileBytes];
-  __shared__ __attribute__((aligned(1024))) char do_tile[kTileBytes];
-  __shared__ __attribute__((aligned(16))) float lse_tile[kTileRows];
-  __shared__ __attribute__((aligned(16))) float delta_tile[kTileRows];
+__global__ void __launch_bounds__(NWAVES * 64, 1) attn_dkv_kernel(AttnArgs a) {
+  __shared__ __attribute__((aligned(1024))) char stage0[2 * kTileBytes];  // Q tile, dO tile
+  __shared__ __attribute__((aligned(1024))) char stage1[2 * kTileBytes];
+  __shared__ __attribute__((aligned(16))) float stats0[2 * kTileRows];  // lse * log2(e), delta
+  __shared__ __attribute__((aligned(16))) float stats1[2 * kTileRows];
   const int lane = threadIdx.x & 63, hf = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int L = a.length, H = a.heads;
@@ -378,34 +407,38 @@ __global__ void __launch_bounds__(NWAVES * 64) attn_dkv_kernel(AttnArgs a) {
     dv[i] = zero16();
   }
 
-  const int q_begin = a.causal ? (kvblk0 / kTileRows) * kTileRows : 0;  // earlier queries see none of these rows
-  for (int q0 = q_begin; q0 < L; q0 += kTileRows) {
-    __syncthreads();
-    load_tile<NWAVES>(qb, (uint32_t)(rs * 2), q0, L, q_tile, wave, lane);
-    load_tile<NWAVES>(dob, (uint32_t)(rs * 2), q0, L, do_tile, wave, lane);
+  const int t_begin = a.causal ? kvblk0 / kTileRows : 0;  // earlier queries see none of these rows
+  const int t_end = (L + kTileRows - 1) / kTileRows;
+  auto issue = [&](int t, char* st, float* stats) {
+    const int q0 = t * kTileRows;
+    load_tile<NWAVES>(qb, (uint32_t)(rs * 2), q0, L, st, wave, lane);
+    load_tile<NWAVES>(dob, (uint32_t)(rs * 2), q0, L, st + kTileBytes, wave, lane);
     if (threadIdx.x < kTileRows) {
       const int qi = min(q0 + (int)threadIdx.x, L - 1);
-      lse_tile[threadIdx.x] = lse_row[qi] * kLog2e;
-      delta_tile[threadIdx.x] = delta_row[qi];
+      stats[threadIdx.x] = lse_row[qi] * kLog2e;
+      stats[kTileRows + threadIdx.x] = delta_row[qi];
     }
-    wait_loads_then_barrier();
-    if (a.causal && q0 + kTileRows - 1 < kvblk0 + wave * 32) continue;  // all queries precede this wave's rows
-
+  };
+  auto process = [&](int t, const char* st, const float* stats) {
+    const int q0 = t * kTileRows;
+    const char *qt_ = st, *dot_ = st + kTileBytes;
+    const float *lset_ = stats, *delt_ = stats + kTileRows;
+    if (a.causal && q0 + kTileRows - 1 < kvblk0 + wave * 32) return;  // all queries precede this wave's rows
     bf16x8 pf[4], dsf[4];
 #pragma unroll
     for (int qblk = 0; qblk < 2; ++qblk) {
       f32x16 s = zero16(), dp = zero16();
 #pragma unroll
       for (int ks = 0; ks < 8; ++ks) {
-        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rows_frag(q_tile, qblk * 32, ks, lane), kf[ks], s, 0, 0, 0);
-        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rows_frag(do_tile, qblk * 32, ks, lane), vf[ks], dp, 0, 0, 0);
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rows_frag(qt_, qblk * 32, ks, lane), kf[ks], s, 0, 0, 0);
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rows_frag(dot_, qblk * 32, ks, lane), vf[ks], dp, 0, 0, 0);
       }
       float p[16], ds[16];
 #pragma unroll
       for (int g4 = 0; g4 < 4; ++g4) {
         const int r0 = qblk * 32 + g4 * 8 + hf * 4;  // 4 consecutive query rows of this group
-        const f32x4 l4 = *LDS_PTR(const f32x4, reinterpret_cast<const char*>(lse_tile) + r0 * 4);
-        const f32x4 d4 = *LDS_PTR(const f32x4, reinterpret_cast<const char*>(delta_tile) + r0 * 4);
+        const f32x4 l4 = *LDS_PTR(const f32x4, reinterpret_cast<const char*>(lset_) + r0 * 4);
+        const f32x4 d4 = *LDS_PTR(const f32x4, reinterpret_cast<const char*>(delt_) + r0 * 4);
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const int jj = g4 * 4 + e;
@@ -425,11 +458,21 @@ __global__ void __launch_bounds__(NWAVES * 64) attn_dkv_kernel(AttnArgs a) {
     for (int blk = 0; blk < 4; ++blk)
 #pragma unroll
       for (int t = 0; t < 4; ++t) {
-        dv[blk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cols_frag(do_tile, blk * 32, t * 16, lane), pf[t],
+        dv[blk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cols_frag(dot_, blk * 32, t * 16, lane), pf[t],
                                                           dv[blk], 0, 0, 0);
-        dk[blk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cols_frag(q_tile, blk * 32, t * 16, lane), dsf[t],
+        dk[blk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cols_frag(qt_, blk * 32, t * 16, lane), dsf[t],
                                                           dk[blk], 0, 0, 0);
       }
+  };
+  issue(t_begin, stage0, stats0);
+  for (int t = t_begin; t < t_end; t += 2) {
+    wait_loads_then_barrier();
+    if (t + 1 < t_end) issue(t + 1, stage1, stats1);
+    process(t, stage0, stats0);
+    if (t + 1 >= t_end) break;
+    wait_loads_then_barrier();
+    if (t + 2 < t_end) issue(t + 2, stage0, stats0);
+    process(t + 1, stage1, stats1);
   }
   store_rows_bf16(a.out0 + head0, rs, kv_lane, L, dk, 1.f, lane);
   store_rows_bf16(a.out1 + head0, rs, kv_lane, L, dv, 1.f, lane);
@@ -456,19 +499,29 @@ AttnArgs make_args(const AttnShape& s) {
 
 }  // namespace
 
+// Query (or memory) rows per workgroup: 128 when that still gives every CU a workgroup, else 64.
+static int waves_per_group(const AttnShape& s) {
+  return ceil_div(s.length, 128) * s.heads * s.batch >= 256 ? 4 : 2;
+}
+
 int attn_fwd_launch(const AttnShape& s, const bf16_t* q, const bf16_t* k, const bf16_t* v,
                     bf16_t* ctx, float* lse, hipStream_t stream) {
   if (int rc = check_shape(s)) return rc;
   AttnArgs a = make_args(s);
   a.q = q; a.k = k; a.v = v; a.out0 = ctx; a.lse_out = lse;
-  // 64 query rows per workgroup keeps >= 256 workgroups in flight at the shard sizes of interest
-  dim3 grid((unsigned)ceil_div(s.length, 64), (unsigned)s.heads, (unsigned)s.batch);
   // algorithmic work: two contractions over the visible (l, m) pairs
   const double pairs = s.causal ? 0.5 * s.length * (s.length + 1.0) : (double)s.length * s.length;
   const double flops = 2.0 * 2.0 * s.batch * s.heads * pairs * kHeadDim;
   const double bytes = 4.0 * s.batch * s.length * s.heads * kRowBytes;
-  LaunchTimer timer("attn_fwd_kernel<2>", flops, bytes, stream);
-  attn_fwd_kernel<2><<<grid, 128, 0, stream>>>(a);
+  const int nw = waves_per_group(s);
+  dim3 grid((unsigned)ceil_div(s.length, nw * 32), (unsigned)s.heads, (unsigned)s.batch);
+  if (nw == 4) {
+    LaunchTimer timer("attn_fwd_kernel<4>", flops, bytes, stream);
+    attn_fwd_kernel<4><<<grid, 256, 0, stream>>>(a);
+  } else {
+    LaunchTimer timer("attn_fwd_kernel<2>", flops, bytes, stream);
+    attn_fwd_kernel<2><<<grid, 128, 0, stream>>>(a);
+  }
   return launch_status("attn_fwd_kernel");
 }
 
@@ -487,18 +540,25 @@ int attn_bwd_launch(const AttnShape& s, const bf16_t* q, const bf16_t* k, const 
   if (int rc = launch_status("attn_delta_kernel")) return rc;
   AttnArgs a = make_args(s);
   a.q = q; a.k = k; a.v = v; a.dctx = dctx; a.lse_in = lse; a.delta_in = delta;
-  dim3 grid((unsigned)ceil_div(s.length, 64), (unsigned)s.heads, (unsigned)s.batch);
+  const int nw = waves_per_group(s);
+  dim3 grid((unsigned)ceil_div(s.length, nw * 32), (unsigned)s.heads, (unsigned)s.batch);
   a.out0 = dq;
-  {  // dq = einsum(ds, k): 1 of the 4 backward contractions (dp and the recomputed logits are overhead here)
-    LaunchTimer timer("attn_dq_kernel<2>", unit, 5.0 * act, stream);
-    attn_dq_kernel<2><<<grid, 128, 0, stream>>>(a);
+  {  // dq = einsum(ds, k): 1 of the 4 backward contractions (the recomputed logits and dp are overhead here)
+    LaunchTimer timer(nw == 4 ? "attn_dq_kernel<4>" : "attn_dq_kernel<2>", unit, 5.0 * act, stream);
+    if (nw == 4)
+      attn_dq_kernel<4><<<grid, 256, 0, stream>>>(a);
+    else
+      attn_dq_kernel<2><<<grid, 128, 0, stream>>>(a);
   }
   if (int rc = launch_status("attn_dq_kernel")) return rc;
   a.out0 = dk;
   a.out1 = dv;
   {  // dp, dv, dk: 3 of the 4 backward contractions
-    LaunchTimer timer("attn_dkv_kernel<2>", 3.0 * unit, 6.0 * act, stream);
-    attn_dkv_kernel<2><<<grid, 128, 0, stream>>>(a);
+    LaunchTimer timer(nw == 4 ? "attn_dkv_kernel<4>" : "attn_dkv_kernel<2>", 3.0 * unit, 6.0 * act, stream);
+    if (nw == 4)
+      attn_dkv_kernel<4><<<grid, 256, 0, stream>>>(a);
+    else
+      attn_dkv_kernel<2><<<grid, 128, 0, stream>>>(a);
   }
   return launch_status("attn_dkv_kernel");
 }

@@ -7,6 +7,7 @@
 namespace mtf {
 
 constexpr int kMaxSegments = 3;
+constexpr int kLargeTileMinCount = 192;  // fewer 256x256 tiles than this: use 128x128 tiles
 
 // C[z][m][n] (+)= alpha * sum_s sum_k A_s[z][m][k] * B_s[z][k][n], then the epilogue.
 //
@@ -32,6 +33,9 @@ struct GemmDesc {
   // batch: z = z0 * batch1 + z1
   int64_t batch0 = 1, batch1 = 1;
   int64_t sA0 = 0, sA1 = 0, sB0 = 0, sB1 = 0, sC0 = 0, sC1 = 0;
+  int tile = 0;  // 0 = choose by output size, 1 = 128x128 tiles, 2 = 256x256 tiles
+  // tuning aid: if set, workgroup 0 stores {shader-clock ticks, 100 MHz ticks} spent in the kernel
+  uint64_t* debug_clocks = nullptr;
 };
 
 // True when the MFMA kernel can run this problem (alignment and divisibility of the leading

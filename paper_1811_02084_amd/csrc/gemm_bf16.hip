@@ -3,10 +3,12 @@
 // "computation time is dominated by that of einsum operations").
 //
 // Design (MI355X):
-//   * one workgroup = 8 wavefronts (2 per SIMD) computes a 256x256 tile of C, K advanced 64 at
-//     a time; each wave owns 128x64 of it as 4x2 accumulators of v_mfma_f32_32x32x16_bf16;
+//   * large tile: one workgroup = 8 wavefronts (2 per SIMD) computes 256x256 of C, K advanced 64
+//     at a time; each wave owns 128x64 as 4x2 accumulators of v_mfma_f32_32x32x16_bf16;
+//     small tile (outputs with too few large tiles to fill 256 CUs): 128x128 by 4 waves of 64x64,
+//     two workgroups per CU;
 //   * operand tiles go global -> LDS directly (global_load_lds_dwordx4, 16 B per lane, no VGPR
-//     staging), double-buffered: 2 stages x (32 KiB A + 32 KiB B) = 128 of the CU's 160 KiB;
+//     staging), double-buffered: large 2 x (32 + 32) KiB = 128 of the CU's 160 KiB, small 64 KiB;
 //   * because those loads place lane i's 16 B at slot i of a 1 KiB run, bank-conflict avoidance
 //     is done by permuting WHICH 16-byte chunk each lane fetches (XOR swizzle), not by padding;
 //   * a k-contiguous operand is read back with ds_read_b128 (8 consecutive k for one row);
@@ -21,6 +23,8 @@
 
 #include "timing.h"
 
+#include <cstdio>
+
 namespace mtf {
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
@@ -32,13 +36,19 @@ typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
 
 namespace {
 
-constexpr int BM = 256, BN = 256, BK = 64;
-constexpr int kThreads = 512;
-constexpr int kATile = BM * BK * 2;         // bytes
-constexpr int kStage = (BM + BN) * BK * 2;  // bytes
-constexpr int kGroupM = 4;                  // tile rows per L2 patch
+constexpr int BK = 64;
 
-__device__ __attribute__((aligned(16))) uint32_t g_zero_chunk[4] = {0u, 0u, 0u, 0u};
+template <int BM_, int BN_, int WM_, int WN_, int GROUP_M_>
+struct TileCfg {
+  static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_;
+  static constexpr int kWaves = WM * WN, kThreads = kWaves * 64;
+  static constexpr int TM = BM / WM / 32, TN = BN / WN / 32;  // 32x32 accumulators per wave
+  static constexpr int kATile = BM * BK * 2, kBTile = BN * BK * 2, kStage = kATile + kBTile;  // bytes
+  static constexpr int kGroupM = GROUP_M_;  // tile rows per L2 patch
+  static constexpr int kWavesPerSimd = 2;  // register budget: two wavefronts per SIMD
+};
+using LargeTile = TileCfg<256, 256, 2, 4, 4>;
+using SmallTile = TileCfg<128, 128, 2, 2, 8>;
 
 struct GemmArgs {
   const bf16_t* A[kMaxSegments];
@@ -54,6 +64,7 @@ struct GemmArgs {
   int tiles_m, tiles_n;
   int batch1;
   int64_t sA0, sA1, sB0, sB1, sC0, sC1;
+  uint64_t* debug_clocks;
 };
 
 // Direct global -> LDS load of 16 bytes per lane: lane i's bytes land at lds_addr + 16*i.
@@ -77,21 +88,25 @@ __device__ __forceinline__ uint32_t lds_address(const char* p) {
   return (uint32_t)(uintptr_t)LDS_PTR(const char, p);
 }
 
-// One operand tile (256 rows of the M/N index x 64 of k) global -> LDS: 4 loads per lane.
+// One operand tile (ROWS of the M/N index x 64 of k) global -> LDS, in 1 KiB runs (one wave-wide
+// load each), ROWS/8/NWAVES loads per lane.
 //   k-contiguous: LDS row = one m (or n), 128 B = 8 chunks; chunk c of row r sits at c ^ ((r>>1)&7)
-//   mn-contiguous: LDS row = one k, 512 B = 32 chunks; chunk c of row k sits at c ^ ((k&3)<<2)
-// TileLoader keeps, per lane, the four loop-invariant byte offsets of its chunks relative to the
-// tile's first element (rows / columns beyond the matrix edge are clamped to the last valid one:
-// they only feed C elements that are never stored); the tile origin itself is wave-uniform.
-template <bool KCONTIG>
+//   mn-contiguous: LDS row = one k, 2*ROWS B; chunk c of row k sits at c ^ ((k&3)<<2)
+// TileLoader keeps, per lane, the loop-invariant byte offsets of its chunks relative to the tile's
+// first element (rows / columns beyond the matrix edge are clamped to the last valid one: they
+// only feed C elements that are never stored); the tile origin itself is wave-uniform.
+template <bool KCONTIG, int ROWS, int NWAVES>
 struct TileLoader {
-  uint32_t off[4];  // byte offset of this lane's chunk i from the tile origin (k0 = 0)
-  int kpos[4];      // k of the chunk (k-contiguous) or k-row (mn-contiguous), relative to k0
+  static constexpr int NL = ROWS / 8 / NWAVES;   // loads per lane per tile
+  static constexpr int CPR = ROWS / 8;           // mn-contiguous: 16-byte chunks per k-row
+  static constexpr int RPR = 64 / CPR;           // mn-contiguous: k-rows per run
+  uint32_t off[NL];  // byte offset of this lane's chunk i from the tile origin (k0 = 0)
+  int kpos[NL];      // k of the chunk (k-contiguous) or k-row (mn-contiguous), relative to k0
 
   __device__ __forceinline__ void init(int64_t ld, int mn0, int mn_limit, int wave, int lane) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int run = i * 8 + wave;
+    for (int i = 0; i < NL; ++i) {
+      const int run = i * NWAVES + wave;
       if (KCONTIG) {
         const int r = run * 8 + (lane >> 3);
         const int c = (lane & 7) ^ ((r >> 1) & 7);
@@ -99,8 +114,8 @@ struct TileLoader {
         off[i] = (uint32_t)((int64_t)mn * ld * 2 + c * 16);
         kpos[i] = c * 8;
       } else {
-        const int kr = run * 2 + (lane >> 5);
-        const int c = (lane & 31) ^ ((kr & 3) << 2);
+        const int kr = run * RPR + lane / CPR;
+        const int c = (lane % CPR) ^ ((kr & 3) << 2);
         const int mn = min(mn0 + c * 8, mn_limit - 8) - mn0;
         off[i] = (uint32_t)((int64_t)kr * ld * 2 + mn * 2);
         kpos[i] = kr;
@@ -113,11 +128,12 @@ struct TileLoader {
                                         int k_left) const {
     if (k_left >= BK) {
 #pragma unroll
-      for (int i = 0; i < 4; ++i) load16_to_lds(origin, off[i], lds_address(tile) + (i * 8 + wave) * 1024);
+      for (int i = 0; i < NL; ++i)
+        load16_to_lds(origin, off[i], lds_address(tile) + (i * NWAVES + wave) * 1024);
     } else {  // ragged last k-tile: chunks past K become zeros
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        char* run = tile + (i * 8 + wave) * 1024;
+      for (int i = 0; i < NL; ++i) {
+        char* run = tile + (i * NWAVES + wave) * 1024;
         if (kpos[i] < k_left)
           load16_to_lds(origin, off[i], lds_address(run));
         else
@@ -129,7 +145,7 @@ struct TileLoader {
 
 // MFMA operand fragment for 32 consecutive m (or n) starting at mn_base and the 16 k of step ks:
 // lane l gets index mn_base + l%32 and k = ks*16 + (l/32)*8 + 0..7.
-template <bool KCONTIG>
+template <bool KCONTIG, int ROWS>
 __device__ __forceinline__ bf16x8 read_fragment(const char* tile, int mn_base, int ks, int lane) {
   if (KCONTIG) {
     const int r = mn_base + (lane & 31);
@@ -138,34 +154,37 @@ __device__ __forceinline__ bf16x8 read_fragment(const char* tile, int mn_base, i
   } else {
     // Transpose load: in each group of 16 lanes, lane j points at 4 consecutive n of k-row j/4;
     // the hardware hands lane i the 4 k-values of column i.
+    constexpr int kPitch = ROWS * 2;
     const int g = lane >> 4, j = lane & 15;
     const int n = mn_base + (g & 1) * 16 + (j & 3) * 4;
     const int krow = ks * 16 + (g >> 1) * 8 + (j >> 2);
     const int chunk = (n >> 3) ^ ((j >> 2) << 2);  // (krow & 3) == j >> 2
-    const char* p = tile + krow * 512 + (chunk << 4) + (n & 7) * 2;
+    const char* p = tile + krow * kPitch + (chunk << 4) + (n & 7) * 2;
     union {
       s16x4 h[2];
       bf16x8 v;
     } u;
     u.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, p));
-    u.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, p + 4 * 512));
+    u.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, p + 4 * kPitch));
     return u.v;
   }
 }
 
-template <bool A_K, bool B_K, int EPI, bool OUT_BF16>
-__global__ void __launch_bounds__(kThreads) gemm_bf16_kernel(GemmArgs g) {
+template <class Cfg, bool A_K, bool B_K, int EPI, bool OUT_BF16>
+__global__ void __launch_bounds__(Cfg::kThreads, Cfg::kWavesPerSimd) gemm_bf16_kernel(GemmArgs g) {
+  constexpr int BM = Cfg::BM, BN = Cfg::BN, TM = Cfg::TM, TN = Cfg::TN;
   // Two stages, used alternately by the twice-unrolled k loop below.
-  __shared__ __attribute__((aligned(1024))) char stage0[kStage];
-  __shared__ __attribute__((aligned(1024))) char stage1[kStage];
+  __shared__ __attribute__((aligned(1024))) char stage0[Cfg::kStage];
+  __shared__ __attribute__((aligned(1024))) char stage1[Cfg::kStage];
 
+  const uint64_t t_start = g.debug_clocks ? clock64() : 0, w_start = g.debug_clocks ? wall_clock64() : 0;
   // ---- which tile: XCD-aware remap, then patches of kGroupM tile rows
   const int per_xcd = gridDim.x >> 3;
   const int t = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
   if (t >= g.tiles_m * g.tiles_n) return;
-  const int per_group = kGroupM * g.tiles_n;
-  const int first_m = (t / per_group) * kGroupM;
-  const int rows = min(g.tiles_m - first_m, kGroupM);
+  const int per_group = Cfg::kGroupM * g.tiles_n;
+  const int first_m = (t / per_group) * Cfg::kGroupM;
+  const int rows = min(g.tiles_m - first_m, Cfg::kGroupM);
   const int tile_m = first_m + (t % per_group) % rows;
   const int tile_n = (t % per_group) / rows;
   const int m0 = tile_m * BM, n0 = tile_n * BN;
@@ -176,13 +195,14 @@ __global__ void __launch_bounds__(kThreads) gemm_bf16_kernel(GemmArgs g) {
 
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int wm = wave >> 2, wn = wave & 3;  // 2 x 4 waves, each 128 (m) x 64 (n)
+  const int wm = wave / Cfg::WN, wn = wave % Cfg::WN;  // this wave's (32*TM) x (32*TN) part
+  const int wave_m = wm * (32 * TM), wave_n = wn * (32 * TN);
 
-  f32x16 acc[4][2];
+  f32x16 acc[TM][TN];
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int i = 0; i < TM; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < TN; ++j)
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
@@ -195,8 +215,8 @@ __global__ void __launch_bounds__(kThreads) gemm_bf16_kernel(GemmArgs g) {
     total_tiles += tiles_in_seg[s];
   }
 
-  TileLoader<A_K> load_a;
-  TileLoader<B_K> load_b;
+  TileLoader<A_K, BM, Cfg::kWaves> load_a;
+  TileLoader<B_K, BN, Cfg::kWaves> load_b;
   load_a.init(g.lda, m0, g.M, wave, lane);
   load_b.init(g.ldb, n0, g.N, wave, lane);
   const int64_t a_tile0 = A_K ? (int64_t)m0 * g.lda : m0, a_kstep = A_K ? 1 : g.lda;
@@ -214,21 +234,35 @@ __global__ void __launch_bounds__(kThreads) gemm_bf16_kernel(GemmArgs g) {
     const bf16_t* pa = g.A[s] + offA + a_tile0 + k0 * a_kstep;
     const bf16_t* pb = g.B[s] + offB + b_tile0 + k0 * b_kstep;
     load_a.issue(reinterpret_cast<const char*>(pa), st, wave, lane, g.K[s] - k0);
-    load_b.issue(reinterpret_cast<const char*>(pb), st + kATile, wave, lane, g.K[s] - k0);
+    load_b.issue(reinterpret_cast<const char*>(pb), st + Cfg::kATile, wave, lane, g.K[s] - k0);
   };
+  // One k-tile = 4 steps of 16.  The fragments of step ks+1 are read from LDS while the MFMAs of
+  // step ks run: one LDS read is slotted in front of each of the first TM+TN MFMAs of a step.
   auto compute = [&](const char* st) {
+    bf16x8 af[2][TM], bf[2][TN];
+#pragma unroll
+    for (int j = 0; j < TN; ++j) bf[0][j] = read_fragment<B_K, BN>(st + Cfg::kATile, wave_n + j * 32, 0, lane);
+#pragma unroll
+    for (int i = 0; i < TM; ++i) af[0][i] = read_fragment<A_K, BM>(st, wave_m + i * 32, 0, lane);
 #pragma unroll
     for (int ks = 0; ks < BK / 16; ++ks) {
-      bf16x8 af[4], bf[2];
+      const int cur = ks & 1, nxt = cur ^ 1;
 #pragma unroll
-      for (int i = 0; i < 4; ++i) af[i] = read_fragment<A_K>(st, wm * 128 + i * 32, ks, lane);
+      for (int i = 0; i < TM; ++i)
 #pragma unroll
-      for (int j = 0; j < 2; ++j) bf[j] = read_fragment<B_K>(st + kATile, wn * 64 + j * 32, ks, lane);
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[j], af[i], acc[i][j], 0, 0, 0);
+        for (int j = 0; j < TN; ++j) {
+          const int slot = i * TN + j;  // MFMA number within the step
+          if (ks + 1 < BK / 16) {
+            if (slot < TN)
+              bf[nxt][slot] = read_fragment<B_K, BN>(st + Cfg::kATile, wave_n + slot * 32, ks + 1, lane);
+            else if (slot < TN + TM)
+              af[nxt][slot - TN] = read_fragment<A_K, BM>(st, wave_m + (slot - TN) * 32, ks + 1, lane);
+          }
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[cur][j], af[cur][i], acc[i][j], 0, 0, 0);
+          // keep this read-then-MFMA order: left alone, the scheduler sinks every read to just
+          // before its first use (fewer live registers) and the overlap is lost
+          __builtin_amdgcn_sched_barrier(0);
+        }
     }
   };
   // Wait for this wave's loads of the tile about to be used, then for everybody's; passing the
@@ -249,17 +283,21 @@ __global__ void __launch_bounds__(kThreads) gemm_bf16_kernel(GemmArgs g) {
     compute(stage1);
   }
 
+  if (g.debug_clocks && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) {
+    g.debug_clocks[0] = clock64() - t_start;
+    g.debug_clocks[1] = wall_clock64() - w_start;
+  }
   // ---- epilogue: lane holds row m = .. + lane%32 and, per group q, 4 consecutive n
   const int lane_m = lane & 31, lane_h = lane >> 5;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int m = m0 + wm * 128 + i * 32 + lane_m;
+  for (int i = 0; i < TM; ++i) {
+    const int m = m0 + wave_m + i * 32 + lane_m;
     if (m >= g.M) continue;
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
+    for (int j = 0; j < TN; ++j) {
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
-        const int n = n0 + wn * 64 + j * 32 + q * 8 + lane_h * 4;
+        const int n = n0 + wave_n + j * 32 + q * 8 + lane_h * 4;
         if (n >= g.N) continue;
         const int64_t idx = offC + (int64_t)m * g.ldc + n;
         float v[4];
@@ -285,8 +323,7 @@ __global__ void __launch_bounds__(kThreads) gemm_bf16_kernel(GemmArgs g) {
           for (int e = 0; e < 4; ++e) v[e] = fmaxf(v[e], 0.f);
         } else if (EPI == MTF_EPI_MASK_GT0) {
           uint2 a = *reinterpret_cast<const uint2*>(g.aux + idx);
-          // bf16 > 0  <=>  sign bit clear and magnitude non-zero (NaN counts as not > 0 is not
-          // needed here: the activations are finite)
+          // bf16 > 0  <=>  sign bit clear and magnitude non-zero
           const uint32_t w[4] = {a.x & 0xffffu, a.x >> 16, a.y & 0xffffu, a.y >> 16};
 #pragma unroll
           for (int e = 0; e < 4; ++e) v[e] = (w[e] != 0u && w[e] < 0x8000u) ? v[e] : 0.f;
@@ -301,42 +338,51 @@ __global__ void __launch_bounds__(kThreads) gemm_bf16_kernel(GemmArgs g) {
   }
 }
 
-template <bool A_K, bool B_K, int EPI, bool OUT_BF16>
-int launch_instance(const GemmArgs& a, dim3 grid, hipStream_t stream) {
+template <class Cfg, bool A_K, bool B_K, int EPI, bool OUT_BF16>
+int launch_instance(const GemmArgs& a, int batch, hipStream_t stream) {
   // name as a profiler prints the instantiation
-  static const char* const kName =
-      A_K ? (B_K ? (OUT_BF16 ? (EPI == 0 ? "gemm_bf16_kernel<true, true, 0, true>" : EPI == 1 ? "gemm_bf16_kernel<true, true, 1, true>" : "gemm_bf16_kernel<true, true, 2, true>")
-                             : (EPI == 0 ? "gemm_bf16_kernel<true, true, 0, false>" : EPI == 1 ? "gemm_bf16_kernel<true, true, 1, false>" : "gemm_bf16_kernel<true, true, 2, false>"))
-                 : (OUT_BF16 ? (EPI == 0 ? "gemm_bf16_kernel<true, false, 0, true>" : EPI == 1 ? "gemm_bf16_kernel<true, false, 1, true>" : "gemm_bf16_kernel<true, false, 2, true>")
-                             : (EPI == 0 ? "gemm_bf16_kernel<true, false, 0, false>" : EPI == 1 ? "gemm_bf16_kernel<true, false, 1, false>" : "gemm_bf16_kernel<true, false, 2, false>")))
-          : (B_K ? (OUT_BF16 ? (EPI == 0 ? "gemm_bf16_kernel<false, true, 0, true>" : EPI == 1 ? "gemm_bf16_kernel<false, true, 1, true>" : "gemm_bf16_kernel<false, true, 2, true>")
-                             : (EPI == 0 ? "gemm_bf16_kernel<false, true, 0, false>" : EPI == 1 ? "gemm_bf16_kernel<false, true, 1, false>" : "gemm_bf16_kernel<false, true, 2, false>"))
-                 : (OUT_BF16 ? (EPI == 0 ? "gemm_bf16_kernel<false, false, 0, true>" : EPI == 1 ? "gemm_bf16_kernel<false, false, 1, true>" : "gemm_bf16_kernel<false, false, 2, true>")
-                             : (EPI == 0 ? "gemm_bf16_kernel<false, false, 0, false>" : EPI == 1 ? "gemm_bf16_kernel<false, false, 1, false>" : "gemm_bf16_kernel<false, false, 2, false>")));
+  static char name[96] = "";
+  if (!name[0])
+    std::snprintf(name, sizeof name, "gemm_bf16_kernel<TileCfg<%d, %d, %d, %d, %d>, %s, %s, %d, %s>", Cfg::BM,
+                  Cfg::BN, Cfg::WM, Cfg::WN, Cfg::kGroupM, A_K ? "true" : "false", B_K ? "true" : "false", EPI,
+                  OUT_BF16 ? "true" : "false");
+  GemmArgs args = a;
+  args.tiles_m = (int)ceil_div(a.M, Cfg::BM);
+  args.tiles_n = (int)ceil_div(a.N, Cfg::BN);
+  const int64_t tiles = (int64_t)args.tiles_m * args.tiles_n;
+  if (tiles > (1 << 28)) return fail(MTF_ERR_UNSUPPORTED, "too many tiles");
+  dim3 grid((unsigned)(ceil_div(tiles, 8) * 8), (unsigned)batch, 1);
   double ktot = 0;
   for (int s = 0; s < a.nseg; ++s) ktot += a.K[s];
-  const double batch = grid.y;
   const double flops = 2.0 * a.M * a.N * ktot * batch;
   const double bytes = batch * (2.0 * ktot * (a.M + a.N) + (double)a.M * a.N * (OUT_BF16 ? 2 : 4));
-  LaunchTimer timer(kName, flops, bytes, stream);
-  gemm_bf16_kernel<A_K, B_K, EPI, OUT_BF16><<<grid, kThreads, 0, stream>>>(a);
+  LaunchTimer timer(name, flops, bytes, stream);
+  gemm_bf16_kernel<Cfg, A_K, B_K, EPI, OUT_BF16><<<grid, Cfg::kThreads, 0, stream>>>(args);
   return launch_status("gemm_bf16_kernel");
 }
 
-template <bool A_K, bool B_K>
-int launch_layout(const GemmDesc& d, const GemmArgs& a, dim3 grid, hipStream_t s) {
+template <class Cfg, bool A_K, bool B_K>
+int launch_layout(const GemmDesc& d, const GemmArgs& a, int batch, hipStream_t s) {
   if (d.out_bf16) {
     switch (d.epi) {
-      case MTF_EPI_NONE: return launch_instance<A_K, B_K, MTF_EPI_NONE, true>(a, grid, s);
-      case MTF_EPI_RELU: return launch_instance<A_K, B_K, MTF_EPI_RELU, true>(a, grid, s);
-      default: return launch_instance<A_K, B_K, MTF_EPI_MASK_GT0, true>(a, grid, s);
+      case MTF_EPI_NONE: return launch_instance<Cfg, A_K, B_K, MTF_EPI_NONE, true>(a, batch, s);
+      case MTF_EPI_RELU: return launch_instance<Cfg, A_K, B_K, MTF_EPI_RELU, true>(a, batch, s);
+      default: return launch_instance<Cfg, A_K, B_K, MTF_EPI_MASK_GT0, true>(a, batch, s);
     }
   }
   switch (d.epi) {
-    case MTF_EPI_NONE: return launch_instance<A_K, B_K, MTF_EPI_NONE, false>(a, grid, s);
-    case MTF_EPI_RELU: return launch_instance<A_K, B_K, MTF_EPI_RELU, false>(a, grid, s);
-    default: return launch_instance<A_K, B_K, MTF_EPI_MASK_GT0, false>(a, grid, s);
+    case MTF_EPI_NONE: return launch_instance<Cfg, A_K, B_K, MTF_EPI_NONE, false>(a, batch, s);
+    case MTF_EPI_RELU: return launch_instance<Cfg, A_K, B_K, MTF_EPI_RELU, false>(a, batch, s);
+    default: return launch_instance<Cfg, A_K, B_K, MTF_EPI_MASK_GT0, false>(a, batch, s);
   }
+}
+
+template <class Cfg>
+int launch_cfg(const GemmDesc& d, const GemmArgs& a, int batch, hipStream_t s) {
+  if (d.a_kcontig && d.b_kcontig) return launch_layout<Cfg, true, true>(d, a, batch, s);
+  if (d.a_kcontig) return launch_layout<Cfg, true, false>(d, a, batch, s);
+  if (d.b_kcontig) return launch_layout<Cfg, false, true>(d, a, batch, s);
+  return launch_layout<Cfg, false, false>(d, a, batch, s);
 }
 
 }  // namespace
@@ -375,17 +421,17 @@ int gemm_bf16_launch(const GemmDesc& d, hipStream_t stream) {
   a.aux = d.aux;
   a.alpha = d.alpha;
   a.accumulate = d.accumulate ? 1 : 0;
-  a.tiles_m = (int)ceil_div(d.M, BM);
-  a.tiles_n = (int)ceil_div(d.N, BN);
+  a.tiles_m = a.tiles_n = 0;
   a.batch1 = (int)d.batch1;
+  a.debug_clocks = d.debug_clocks;
   a.sA0 = d.sA0; a.sA1 = d.sA1; a.sB0 = d.sB0; a.sB1 = d.sB1; a.sC0 = d.sC0; a.sC1 = d.sC1;
-  const int64_t tiles = (int64_t)a.tiles_m * a.tiles_n;
-  if (tiles > (1 << 28)) return fail(MTF_ERR_UNSUPPORTED, "too many tiles");
-  dim3 grid((unsigned)(ceil_div(tiles, 8) * 8), (unsigned)(d.batch0 * d.batch1), 1);
-  if (d.a_kcontig && d.b_kcontig) return launch_layout<true, true>(d, a, grid, stream);
-  if (d.a_kcontig) return launch_layout<true, false>(d, a, grid, stream);
-  if (d.b_kcontig) return launch_layout<false, true>(d, a, grid, stream);
-  return launch_layout<false, false>(d, a, grid, stream);
+  const int batch = (int)(d.batch0 * d.batch1);
+  // Tile choice: the large tile moves half the bytes per flop, but needs enough tiles to occupy
+  // the 256 CUs; below that the small tile (4x the tiles, two workgroups per CU) wins.
+  const int64_t large_tiles = ceil_div(d.M, LargeTile::BM) * ceil_div(d.N, LargeTile::BN) * batch;
+  int tile = d.tile;
+  if (tile == 0) tile = large_tiles >= kLargeTileMinCount ? 2 : 1;
+  return tile == 2 ? launch_cfg<LargeTile>(d, a, batch, stream) : launch_cfg<SmallTile>(d, a, batch, stream);
 }
 
 }  // namespace mtf
