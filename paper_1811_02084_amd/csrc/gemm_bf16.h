@@ -7,6 +7,7 @@
 namespace mtf {
 
 constexpr int kMaxSegments = 3;
+constexpr int kMaxGroup = 4;
 constexpr int kLargeTileMinCount = 192;  // fewer 256x256 tiles than this: use 128x128 tiles
 
 // C[z][m][n] (+)= alpha * sum_s sum_k A_s[z][m][k] * B_s[z][k][n], then the epilogue.
@@ -33,6 +34,17 @@ struct GemmDesc {
   // batch: z = z0 * batch1 + z1
   int64_t batch0 = 1, batch1 = 1;
   int64_t sA0 = 0, sA1 = 0, sB0 = 0, sB1 = 0, sC0 = 0, sC1 = 0;
+  // Grouped launch: up to kMaxGroup - 1 further independent problems with the same operand
+  // layouts, epilogue (NONE only), output dtype and alpha run in the same launch, so that several
+  // small outputs fill the machine together.  Requires nseg == 1, no batch, no accumulate.
+  struct Extra {
+    const bf16_t* A = nullptr;
+    const bf16_t* B = nullptr;
+    void* C = nullptr;
+    int64_t M = 0, N = 0, K = 0, lda = 0, ldb = 0, ldc = 0;
+  };
+  int nextra = 0;
+  Extra extra[kMaxGroup - 1];
   int tile = 0;  // 0 = choose by output size, 1 = 128x128 tiles, 2 = 256x256 tiles
   // tuning aid: if set, workgroup 0 stores {shader-clock ticks, 100 MHz ticks} spent in the kernel
   uint64_t* debug_clocks = nullptr;

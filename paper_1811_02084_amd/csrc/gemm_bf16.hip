@@ -50,18 +50,20 @@ struct TileCfg {
 using LargeTile = TileCfg<256, 256, 2, 4, 4>;
 using SmallTile = TileCfg<128, 128, 2, 2, 8>;
 
+// Slot s of A/B/K is k-segment s of one problem (ngroup == 1) or, in a grouped launch, the
+// operands of problem s (then every problem has one segment and its own M, N, C and leading dims).
 struct GemmArgs {
-  const bf16_t* A[kMaxSegments];
-  const bf16_t* B[kMaxSegments];
-  int K[kMaxSegments];
-  int nseg;
-  int M, N;
-  int64_t lda, ldb, ldc;
-  void* C;
+  const bf16_t* A[kMaxGroup];
+  const bf16_t* B[kMaxGroup];
+  int K[kMaxGroup];
+  int nseg, ngroup;
+  int M[kMaxGroup], N[kMaxGroup];
+  int64_t lda[kMaxGroup], ldb[kMaxGroup], ldc[kMaxGroup];
+  void* C[kMaxGroup];
   const bf16_t* aux;
   float alpha;
   int accumulate;
-  int tiles_m, tiles_n;
+  int tiles_m[kMaxGroup], tiles_n[kMaxGroup];
   int batch1;
   int64_t sA0, sA1, sB0, sB1, sC0, sC1;
   uint64_t* debug_clocks;
@@ -179,17 +181,21 @@ __global__ void __launch_bounds__(Cfg::kThreads, Cfg::kWavesPerSimd) gemm_bf16_k
 
   const uint64_t t_start = g.debug_clocks ? clock64() : 0, w_start = g.debug_clocks ? wall_clock64() : 0;
   // ---- which tile: XCD-aware remap, then patches of kGroupM tile rows
+  const int grp = g.ngroup > 1 ? blockIdx.y : 0;  // grouped launch: blockIdx.y picks the problem
+  const int M = g.M[grp], N = g.N[grp], tiles_m = g.tiles_m[grp], tiles_n = g.tiles_n[grp];
+  const int64_t lda = g.lda[grp], ldb = g.ldb[grp], ldc = g.ldc[grp];
   const int per_xcd = gridDim.x >> 3;
   const int t = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-  if (t >= g.tiles_m * g.tiles_n) return;
-  const int per_group = Cfg::kGroupM * g.tiles_n;
+  if (t >= tiles_m * tiles_n) return;
+  const int per_group = Cfg::kGroupM * tiles_n;
   const int first_m = (t / per_group) * Cfg::kGroupM;
-  const int rows = min(g.tiles_m - first_m, Cfg::kGroupM);
+  const int rows = min(tiles_m - first_m, Cfg::kGroupM);
   const int tile_m = first_m + (t % per_group) % rows;
   const int tile_n = (t % per_group) / rows;
   const int m0 = tile_m * BM, n0 = tile_n * BN;
 
-  const int z0 = blockIdx.y / g.batch1, z1 = blockIdx.y % g.batch1;
+  const int zb = g.ngroup > 1 ? 0 : blockIdx.y;
+  const int z0 = zb / g.batch1, z1 = zb % g.batch1;
   const int64_t offA = z0 * g.sA0 + z1 * g.sA1, offB = z0 * g.sB0 + z1 * g.sB1,
                 offC = z0 * g.sC0 + z1 * g.sC1;
 
@@ -211,16 +217,16 @@ __global__ void __launch_bounds__(Cfg::kThreads, Cfg::kWavesPerSimd) gemm_bf16_k
   int total_tiles = 0;
 #pragma unroll
   for (int s = 0; s < kMaxSegments; ++s) {
-    tiles_in_seg[s] = s < g.nseg ? (g.K[s] + BK - 1) / BK : 0;
+    tiles_in_seg[s] = s < g.nseg ? (g.K[grp + s] + BK - 1) / BK : 0;  // grp > 0 only with nseg == 1
     total_tiles += tiles_in_seg[s];
   }
 
   TileLoader<A_K, BM, Cfg::kWaves> load_a;
   TileLoader<B_K, BN, Cfg::kWaves> load_b;
-  load_a.init(g.lda, m0, g.M, wave, lane);
-  load_b.init(g.ldb, n0, g.N, wave, lane);
-  const int64_t a_tile0 = A_K ? (int64_t)m0 * g.lda : m0, a_kstep = A_K ? 1 : g.lda;
-  const int64_t b_tile0 = B_K ? (int64_t)n0 * g.ldb : n0, b_kstep = B_K ? 1 : g.ldb;
+  load_a.init(lda, m0, M, wave, lane);
+  load_b.init(ldb, n0, N, wave, lane);
+  const int64_t a_tile0 = A_K ? (int64_t)m0 * lda : m0, a_kstep = A_K ? 1 : lda;
+  const int64_t b_tile0 = B_K ? (int64_t)n0 * ldb : n0, b_kstep = B_K ? 1 : ldb;
 
   auto issue = [&](int kt, char* st) {
     int s = 0, local = kt;
@@ -231,6 +237,7 @@ __global__ void __launch_bounds__(Cfg::kThreads, Cfg::kWavesPerSimd) gemm_bf16_k
         s = q + 1;
       }
     const int k0 = local * BK;
+    s += grp;
     const bf16_t* pa = g.A[s] + offA + a_tile0 + k0 * a_kstep;
     const bf16_t* pb = g.B[s] + offB + b_tile0 + k0 * b_kstep;
     load_a.issue(reinterpret_cast<const char*>(pa), st, wave, lane, g.K[s] - k0);
@@ -289,29 +296,30 @@ __global__ void __launch_bounds__(Cfg::kThreads, Cfg::kWavesPerSimd) gemm_bf16_k
   }
   // ---- epilogue: lane holds row m = .. + lane%32 and, per group q, 4 consecutive n
   const int lane_m = lane & 31, lane_h = lane >> 5;
+  void* const Cg = g.C[grp];
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
     const int m = m0 + wave_m + i * 32 + lane_m;
-    if (m >= g.M) continue;
+    if (m >= M) continue;
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
         const int n = n0 + wave_n + j * 32 + q * 8 + lane_h * 4;
-        if (n >= g.N) continue;
-        const int64_t idx = offC + (int64_t)m * g.ldc + n;
+        if (n >= N) continue;
+        const int64_t idx = offC + (int64_t)m * ldc + n;
         float v[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) v[e] = g.alpha * acc[i][j][q * 4 + e];
         if (g.accumulate) {
           if (OUT_BF16) {
-            uint2 old = *reinterpret_cast<const uint2*>(static_cast<const bf16_t*>(g.C) + idx);
+            uint2 old = *reinterpret_cast<const uint2*>(static_cast<const bf16_t*>(Cg) + idx);
             v[0] += __uint_as_float(old.x << 16);
             v[1] += __uint_as_float(old.x & 0xffff0000u);
             v[2] += __uint_as_float(old.y << 16);
             v[3] += __uint_as_float(old.y & 0xffff0000u);
           } else {
-            float4 old = *reinterpret_cast<const float4*>(static_cast<const float*>(g.C) + idx);
+            float4 old = *reinterpret_cast<const float4*>(static_cast<const float*>(Cg) + idx);
             v[0] += old.x;
             v[1] += old.y;
             v[2] += old.z;
@@ -329,10 +337,10 @@ __global__ void __launch_bounds__(Cfg::kThreads, Cfg::kWavesPerSimd) gemm_bf16_k
           for (int e = 0; e < 4; ++e) v[e] = (w[e] != 0u && w[e] < 0x8000u) ? v[e] : 0.f;
         }
         if (OUT_BF16)
-          *reinterpret_cast<uint2*>(static_cast<bf16_t*>(g.C) + idx) =
+          *reinterpret_cast<uint2*>(static_cast<bf16_t*>(Cg) + idx) =
               make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
         else
-          *reinterpret_cast<float4*>(static_cast<float*>(g.C) + idx) = make_float4(v[0], v[1], v[2], v[3]);
+          *reinterpret_cast<float4*>(static_cast<float*>(Cg) + idx) = make_float4(v[0], v[1], v[2], v[3]);
       }
     }
   }
@@ -347,15 +355,20 @@ int launch_instance(const GemmArgs& a, int batch, hipStream_t stream) {
                   Cfg::BN, Cfg::WM, Cfg::WN, Cfg::kGroupM, A_K ? "true" : "false", B_K ? "true" : "false", EPI,
                   OUT_BF16 ? "true" : "false");
   GemmArgs args = a;
-  args.tiles_m = (int)ceil_div(a.M, Cfg::BM);
-  args.tiles_n = (int)ceil_div(a.N, Cfg::BN);
-  const int64_t tiles = (int64_t)args.tiles_m * args.tiles_n;
+  int64_t tiles = 0;
+  double flops = 0, bytes = 0;
+  for (int p = 0; p < a.ngroup; ++p) {
+    args.tiles_m[p] = (int)ceil_div(a.M[p], Cfg::BM);
+    args.tiles_n[p] = (int)ceil_div(a.N[p], Cfg::BN);
+    tiles = std::max<int64_t>(tiles, (int64_t)args.tiles_m[p] * args.tiles_n[p]);
+    double ktot = 0;
+    if (a.ngroup > 1) ktot = a.K[p];
+    else for (int s = 0; s < a.nseg; ++s) ktot += a.K[s];
+    flops += 2.0 * a.M[p] * a.N[p] * ktot * batch;
+    bytes += batch * (2.0 * ktot * (a.M[p] + a.N[p]) + (double)a.M[p] * a.N[p] * (OUT_BF16 ? 2 : 4));
+  }
   if (tiles > (1 << 28)) return fail(MTF_ERR_UNSUPPORTED, "too many tiles");
-  dim3 grid((unsigned)(ceil_div(tiles, 8) * 8), (unsigned)batch, 1);
-  double ktot = 0;
-  for (int s = 0; s < a.nseg; ++s) ktot += a.K[s];
-  const double flops = 2.0 * a.M * a.N * ktot * batch;
-  const double bytes = batch * (2.0 * ktot * (a.M + a.N) + (double)a.M * a.N * (OUT_BF16 ? 2 : 4));
+  dim3 grid((unsigned)(ceil_div(tiles, 8) * 8), (unsigned)(a.ngroup > 1 ? a.ngroup : batch), 1);
   LaunchTimer timer(name, flops, bytes, stream);
   gemm_bf16_kernel<Cfg, A_K, B_K, EPI, OUT_BF16><<<grid, Cfg::kThreads, 0, stream>>>(args);
   return launch_status("gemm_bf16_kernel");
@@ -400,37 +413,63 @@ bool gemm_bf16_supported(const GemmDesc& d) {
   }
   if (!aligned16(d.C) || (d.epi == MTF_EPI_MASK_GT0 && (!d.aux || !aligned16(d.aux)))) return false;
   if (d.batch0 * d.batch1 > 65535) return false;
+  if (d.nextra < 0 || d.nextra > kMaxGroup - 1) return false;
+  if (d.nextra > 0 && (d.nseg != 1 || d.batch0 * d.batch1 != 1 || d.accumulate || d.epi != MTF_EPI_NONE))
+    return false;
+  for (int p = 0; p < d.nextra; ++p) {
+    const GemmDesc::Extra& e = d.extra[p];
+    if (e.M <= 0 || e.N <= 0 || e.K < 0 || e.M > INT32_MAX || e.N > INT32_MAX || e.K > INT32_MAX) return false;
+    if (e.lda % 8 || e.ldb % 8 || e.ldc % 4 || e.N % 8 || (!d.a_kcontig && e.M % 8)) return false;
+    if ((d.a_kcontig || d.b_kcontig) && e.K % 8) return false;
+    if (!e.A || !e.B || !e.C || !aligned16(e.A) || !aligned16(e.B) || !aligned16(e.C)) return false;
+  }
   return true;
 }
 
 int gemm_bf16_launch(const GemmDesc& d, hipStream_t stream) {
   if (!gemm_bf16_supported(d)) return fail(MTF_ERR_UNSUPPORTED, "GEMM shape/alignment");
   GemmArgs a;
-  for (int s = 0; s < kMaxSegments; ++s) {
+  for (int s = 0; s < kMaxGroup; ++s) {
     a.A[s] = s < d.nseg ? d.A[s] : d.A[0];
     a.B[s] = s < d.nseg ? d.B[s] : d.B[0];
     a.K[s] = s < d.nseg ? (int)d.K[s] : 0;
+    a.M[s] = (int)d.M;
+    a.N[s] = (int)d.N;
+    a.lda[s] = d.lda;
+    a.ldb[s] = d.ldb;
+    a.ldc[s] = d.ldc;
+    a.C[s] = d.C;
+    a.tiles_m[s] = a.tiles_n[s] = 0;
   }
   a.nseg = d.nseg;
-  a.M = (int)d.M;
-  a.N = (int)d.N;
-  a.lda = d.lda;
-  a.ldb = d.ldb;
-  a.ldc = d.ldc;
-  a.C = d.C;
+  a.ngroup = 1 + d.nextra;
+  for (int p = 0; p < d.nextra; ++p) {
+    const GemmDesc::Extra& e = d.extra[p];
+    a.A[p + 1] = e.A; a.B[p + 1] = e.B; a.C[p + 1] = e.C;
+    a.M[p + 1] = (int)e.M; a.N[p + 1] = (int)e.N; a.K[p + 1] = (int)e.K;
+    a.lda[p + 1] = e.lda; a.ldb[p + 1] = e.ldb; a.ldc[p + 1] = e.ldc;
+  }
   a.aux = d.aux;
   a.alpha = d.alpha;
   a.accumulate = d.accumulate ? 1 : 0;
-  a.tiles_m = a.tiles_n = 0;
   a.batch1 = (int)d.batch1;
   a.debug_clocks = d.debug_clocks;
   a.sA0 = d.sA0; a.sA1 = d.sA1; a.sB0 = d.sB0; a.sB1 = d.sB1; a.sC0 = d.sC0; a.sC1 = d.sC1;
   const int batch = (int)(d.batch0 * d.batch1);
   // Tile choice: the large tile moves half the bytes per flop, but needs enough tiles to occupy
   // the 256 CUs; below that the small tile (4x the tiles, two workgroups per CU) wins.
-  const int64_t large_tiles = ceil_div(d.M, LargeTile::BM) * ceil_div(d.N, LargeTile::BN) * batch;
+  int64_t large_tiles = ceil_div(d.M, LargeTile::BM) * ceil_div(d.N, LargeTile::BN) * batch;
+  for (int p = 0; p < d.nextra; ++p)
+    large_tiles += ceil_div(d.extra[p].M, LargeTile::BM) * ceil_div(d.extra[p].N, LargeTile::BN);
+  int64_t small_tiles = ceil_div(d.M, SmallTile::BM) * ceil_div(d.N, SmallTile::BN) * batch;
+  for (int p = 0; p < d.nextra; ++p)
+    small_tiles += ceil_div(d.extra[p].M, SmallTile::BM) * ceil_div(d.extra[p].N, SmallTile::BN);
+  // rounds of tiles over 256 CUs (large: one workgroup per CU, 4 work units each; small: two
+  // per CU, 1 unit each, at ~0.8 of the large tile's rate)
+  const double cost_large = (double)ceil_div(large_tiles, 256) * 4.0;
+  const double cost_small = (double)ceil_div(small_tiles, 512) * 2.0 / 0.8;
   int tile = d.tile;
-  if (tile == 0) tile = large_tiles >= kLargeTileMinCount ? 2 : 1;
+  if (tile == 0) tile = cost_large <= cost_small ? 2 : 1;
   return tile == 2 ? launch_cfg<LargeTile>(d, a, batch, stream) : launch_cfg<SmallTile>(d, a, batch, stream);
 }
 

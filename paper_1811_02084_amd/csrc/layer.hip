@@ -11,6 +11,8 @@ namespace {
 
 inline size_t round256(size_t n) { return (n + 255) & ~size_t(255); }
 
+constexpr int kLayerPartials = 3;  // fp32 partial-sum buffers a layer step keeps in its workspace
+
 // C[M,N] = A op B with both operands given as plain row-major matrices:
 //   a_kc: A is [M,K] (k contiguous) else [K,M];   b_kc: B is [N,K] (k contiguous) else [K,N].
 GemmDesc gemm(const void* A, bool a_kc, const void* B, bool b_kc, void* C, bool c_bf16, int64_t M,
@@ -29,6 +31,44 @@ GemmDesc gemm(const void* A, bool a_kc, const void* B, bool b_kc, void* C, bool 
   d.C = C;
   d.out_bf16 = c_bf16;
   return d;
+}
+
+// Appends problem `p` (one segment, same layouts / dtype as the group) to a grouped launch.
+void add_to_group(GemmDesc* group, const GemmDesc& p) {
+  GemmDesc::Extra& e = group->extra[group->nextra++];
+  e.A = p.A[0]; e.B = p.B[0]; e.C = p.C;
+  e.M = p.M; e.N = p.N; e.K = p.K[0];
+  e.lda = p.lda; e.ldb = p.ldb; e.ldc = p.ldc;
+}
+
+// Destination of an einsum whose result is wanted as a sum anyway (a partial sum on its way to
+// the Allreduce / residual add): n >= 1 fp32 buffers whose sum is the result.  With n > 1 the
+// contracted dim is cut into n ranges that run as one grouped launch - on this one GPU the same
+// thing the layout does across processors when it splits a reduced-out dim.
+struct Partials {
+  void* buf[kMaxGroup];
+  int n;
+};
+
+// C = A op B with K cut into parts.n equal ranges (K % (8 * n) == 0 required), range i -> buf[i].
+int gemm_k_split(const void* A, bool a_kc, const void* B, bool b_kc, const Partials& parts, int64_t M,
+                 int64_t N, int64_t K, hipStream_t s) {
+  const int n = (parts.n > 1 && K % (8 * parts.n) == 0) ? parts.n : 1;
+  const int64_t kr = K / n;
+  const bf16_t* a = static_cast<const bf16_t*>(A);
+  const bf16_t* b = static_cast<const bf16_t*>(B);
+  GemmDesc g = gemm(a, a_kc, b, b_kc, parts.buf[0], false, M, N, kr);
+  g.lda = a_kc ? K : M;
+  g.ldb = b_kc ? K : N;
+  for (int i = 1; i < n; ++i) {
+    GemmDesc p = gemm(a + (a_kc ? i * kr : i * kr * M), a_kc, b + (b_kc ? i * kr : i * kr * N), b_kc,
+                      parts.buf[i], false, M, N, kr);
+    p.lda = g.lda;
+    p.ldb = g.ldb;
+    add_to_group(&g, p);
+  }
+  if (int rc = gemm_bf16_launch(g, s)) return rc;
+  return n;  // number of buffers actually written (positive)
 }
 
 int check_ptrs(std::initializer_list<const void*> ptrs, const char* what) {
@@ -77,19 +117,20 @@ MhaBwdScratch mha_bwd_scratch(const mtf_mha_dims* d, void* base) {
   return s;
 }
 
+// Returns the number of buffers of `y` written (their sum is y_partial), or a negative error.
 int ffn_fwd(const mtf_ffn_dims* d, const void* x, const void* w_in, const void* w_out, void* a,
-            void* y_partial, hipStream_t s) {
+            const Partials& y, hipStream_t s) {
   const int64_t T = d->batch * d->length, D = d->d_model, F = d->d_ff;
   // a = relu(einsum(x[b,l,D], w_in[D,F] -> [b,l,F]))
   GemmDesc g1 = gemm(x, true, w_in, false, a, true, T, F, D);
   g1.epi = MTF_EPI_RELU;
   if (int rc = gemm_bf16_launch(g1, s)) return rc;
   // y_partial = einsum(a[b,l,F], w_out[F,D] -> [b,l,D]); F is the split, reduced-out dim
-  return gemm_bf16_launch(gemm(a, true, w_out, false, y_partial, false, T, D, F), s);
+  return gemm_k_split(a, true, w_out, false, y, T, D, F, s);
 }
 
 int ffn_bwd(const mtf_ffn_dims* d, const void* x, const void* a, const void* w_in, const void* w_out,
-            const void* dy, void* dw_in, void* dw_out, void* dx_partial, void* dh, hipStream_t s) {
+            const void* dy, void* dw_in, void* dw_out, const Partials& dx, void* dh, hipStream_t s) {
   const int64_t T = d->batch * d->length, D = d->d_model, F = d->d_ff;
   // dw_out = einsum(a[b,l,F], dy[b,l,D] -> [F,D])
   if (int rc = gemm_bf16_launch(gemm(a, false, dy, false, dw_out, false, F, D, T), s)) return rc;
@@ -101,55 +142,82 @@ int ffn_bwd(const mtf_ffn_dims* d, const void* x, const void* a, const void* w_i
   // dw_in = einsum(x[b,l,D], dh[b,l,F] -> [D,F])
   if (int rc = gemm_bf16_launch(gemm(x, false, dh, false, dw_in, false, D, F, T), s)) return rc;
   // dx_partial = einsum(dh[b,l,F], w_in[D,F] -> [b,l,D])
-  return gemm_bf16_launch(gemm(dh, true, w_in, true, dx_partial, false, T, D, F), s);
+  return gemm_k_split(dh, true, w_in, true, dx, T, D, F, s);
 }
 
 int mha_fwd(const mtf_mha_dims* d, const void* x, const void* w_q, const void* w_k, const void* w_v,
             const void* w_o, float scale, int causal, void* q, void* k, void* v, void* ctx, void* lse,
-            void* y_partial, hipStream_t s) {
+            const Partials& y, hipStream_t s) {
   const int64_t T = d->batch * d->length, D = d->d_model, HK = d->heads * d->d_k;
-  // q, k, v = einsum(x[b,l,D], w[D,h,k] -> [b,l,h,k]); D is not split: complete local slices
-  if (int rc = gemm_bf16_launch(gemm(x, true, w_q, false, q, true, T, HK, D), s)) return rc;
-  if (int rc = gemm_bf16_launch(gemm(x, true, w_k, false, k, true, T, HK, D), s)) return rc;
-  if (int rc = gemm_bf16_launch(gemm(x, true, w_v, false, v, true, T, HK, D), s)) return rc;
+  // q, k, v = einsum(x[b,l,D], w[D,h,k] -> [b,l,h,k]); D is not split: complete local slices.
+  // Three independent einsums with one shared operand: one grouped launch.
+  GemmDesc qkv = gemm(x, true, w_q, false, q, true, T, HK, D);
+  add_to_group(&qkv, gemm(x, true, w_k, false, k, true, T, HK, D));
+  add_to_group(&qkv, gemm(x, true, w_v, false, v, true, T, HK, D));
+  if (int rc = gemm_bf16_launch(qkv, s)) return rc;
   AttnShape as{(int)d->batch, (int)d->length, (int)d->heads, scale, causal};
   if (int rc = attn_fwd_launch(as, (const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (bf16_t*)ctx,
                                (float*)lse, s))
     return rc;
   // y_partial = einsum(ctx[b,l,h,v], w_o[h,v,D] -> [b,l,D]); heads is the split, reduced-out dim
-  return gemm_bf16_launch(gemm(ctx, true, w_o, false, y_partial, false, T, D, HK), s);
+  return gemm_k_split(ctx, true, w_o, false, y, T, D, HK, s);
 }
 
 int mha_bwd(const mtf_mha_dims* d, const void* x, const void* w_q, const void* w_k, const void* w_v,
             const void* w_o, const void* q, const void* k, const void* v, const void* ctx,
             const void* lse, const void* dy, float scale, int causal, void* dw_q, void* dw_k,
-            void* dw_v, void* dw_o, void* dx_partial, const MhaBwdScratch& w, hipStream_t s) {
+            void* dw_v, void* dw_o, const Partials& dx, const MhaBwdScratch& w, hipStream_t s) {
   const int64_t T = d->batch * d->length, D = d->d_model, HK = d->heads * d->d_k;
-  // dw_o = einsum(ctx[b,l,h,v], dy[b,l,D] -> [h,v,D])
-  if (int rc = gemm_bf16_launch(gemm(ctx, false, dy, false, dw_o, false, HK, D, T), s)) return rc;
   // dctx = einsum(dy[b,l,D], w_o[h,v,D] -> [b,l,h,v])
   if (int rc = gemm_bf16_launch(gemm(dy, true, w_o, true, w.dctx, true, T, HK, D), s)) return rc;
   AttnShape as{(int)d->batch, (int)d->length, (int)d->heads, scale, causal};
   if (int rc = attn_bwd_launch(as, (const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v,
                                (const bf16_t*)ctx, (const float*)lse, w.dctx, w.dq, w.dk, w.dv, w.delta, s))
     return rc;
-  // dw_{q,k,v} = einsum(x[b,l,D], d{q,k,v}[b,l,h,k] -> [D,h,k])
-  if (int rc = gemm_bf16_launch(gemm(x, false, w.dq, false, dw_q, false, D, HK, T), s)) return rc;
-  if (int rc = gemm_bf16_launch(gemm(x, false, w.dk, false, dw_k, false, D, HK, T), s)) return rc;
-  if (int rc = gemm_bf16_launch(gemm(x, false, w.dv, false, dw_v, false, D, HK, T), s)) return rc;
+  // dw_o = einsum(ctx[b,l,h,v], dy[b,l,D] -> [h,v,D]) and
+  // dw_{q,k,v} = einsum(x[b,l,D], d{q,k,v}[b,l,h,k] -> [D,h,k]): four small outputs that each
+  // reduce out the (long) token dims; launched as one group so that together they fill the CUs
+  GemmDesc dw = gemm(ctx, false, dy, false, dw_o, false, HK, D, T);
+  add_to_group(&dw, gemm(x, false, w.dq, false, dw_q, false, D, HK, T));
+  add_to_group(&dw, gemm(x, false, w.dk, false, dw_k, false, D, HK, T));
+  add_to_group(&dw, gemm(x, false, w.dv, false, dw_v, false, D, HK, T));
+  if (int rc = gemm_bf16_launch(dw, s)) return rc;
   // dx_partial = sum over {q,k,v} of einsum(d*[b,l,h,k], w_*[D,h,k] -> [b,l,D]): one contraction
   // whose reduced dims (h,k) are spread over three tensor pairs
-  GemmDesc g = gemm(w.dq, true, w_q, true, dx_partial, false, T, D, HK);
-  g.nseg = 3;
+  GemmDesc g = gemm(w.dq, true, w_q, true, dx.buf[0], false, T, D, HK);
+  if (dx.n >= 3) {  // the three terms as three partial sums of one grouped launch
+    add_to_group(&g, gemm(w.dk, true, w_k, true, dx.buf[1], false, T, D, HK));
+    add_to_group(&g, gemm(w.dv, true, w_v, true, dx.buf[2], false, T, D, HK));
+    if (int rc = gemm_bf16_launch(g, s)) return rc;
+    return 3;
+  }
+  g.nseg = 3;  // one output: the three (A, B) pairs are consecutive ranges of one reduction
   g.A[1] = w.dk; g.B[1] = static_cast<const bf16_t*>(w_k); g.K[1] = HK;
   g.A[2] = w.dv; g.B[2] = static_cast<const bf16_t*>(w_v); g.K[2] = HK;
-  return gemm_bf16_launch(g, s);
+  if (int rc = gemm_bf16_launch(g, s)) return rc;
+  return 1;
 }
 
-int residual_add(const void* partial, const void* residual_bf16, void* out_bf16, int64_t count,
+// out = residual + sum of the first n buffers of `parts` (bf16 out): the Allreduce point of a
+// one-slice group followed by the residual add.
+int residual_add(const Partials& parts, int n, const void* residual_bf16, void* out_bf16, int64_t count,
                  hipStream_t s) {
-  const void* parts[1] = {partial};
-  return mtf_reduce_partials(parts, 1, residual_bf16, MTF_BF16, out_bf16, MTF_BF16, count, s);
+  return mtf_reduce_partials(parts.buf, n, residual_bf16, MTF_BF16, out_bf16, MTF_BF16, count, s);
+}
+
+Partials single(void* buf) {
+  Partials p{};
+  p.buf[0] = buf;
+  p.n = 1;
+  return p;
+}
+
+// n fp32 buffers of `count` elements carved from a workspace.
+Partials carve(void* base, int n, int64_t count) {
+  Partials p{};
+  p.n = n;
+  for (int i = 0; i < n; ++i) p.buf[i] = static_cast<char*>(base) + (size_t)i * round256((size_t)count * 4);
+  return p;
 }
 
 }  // namespace
@@ -163,7 +231,8 @@ int mtf_ffn_fwd(const mtf_ffn_dims* d, const void* x, const void* w_in, const vo
                 void* y_partial, void* stream) {
   if (int rc = check_ffn(d)) return rc;
   if (int rc = check_ptrs({x, w_in, w_out, a, y_partial}, "mtf_ffn_fwd buffer")) return rc;
-  return ffn_fwd(d, x, w_in, w_out, a, y_partial, static_cast<hipStream_t>(stream));
+  const int rc = ffn_fwd(d, x, w_in, w_out, a, single(y_partial), static_cast<hipStream_t>(stream));
+  return rc < 0 ? rc : MTF_OK;
 }
 
 size_t mtf_ffn_bwd_workspace_bytes(const mtf_ffn_dims* d) {
@@ -178,8 +247,9 @@ int mtf_ffn_bwd(const mtf_ffn_dims* d, const void* x, const void* a, const void*
   if (int rc = check_ptrs({x, a, w_in, w_out, dy, dw_in, dw_out, dx_partial}, "mtf_ffn_bwd buffer")) return rc;
   if (!workspace || workspace_bytes < mtf_ffn_bwd_workspace_bytes(d) || !aligned16(workspace))
     return fail(MTF_ERR_WORKSPACE, "mtf_ffn_bwd needs %zu bytes", mtf_ffn_bwd_workspace_bytes(d));
-  return ffn_bwd(d, x, a, w_in, w_out, dy, dw_in, dw_out, dx_partial, workspace,
-                 static_cast<hipStream_t>(stream));
+  const int rc = ffn_bwd(d, x, a, w_in, w_out, dy, dw_in, dw_out, single(dx_partial), workspace,
+                         static_cast<hipStream_t>(stream));
+  return rc < 0 ? rc : MTF_OK;
 }
 
 int mtf_mha_fwd(const mtf_mha_dims* d, const void* x, const void* w_q, const void* w_k,
@@ -187,8 +257,9 @@ int mtf_mha_fwd(const mtf_mha_dims* d, const void* x, const void* w_q, const voi
                 void* v, void* ctx, void* lse, void* y_partial, void* stream) {
   if (int rc = check_mha(d)) return rc;
   if (int rc = check_ptrs({x, w_q, w_k, w_v, w_o, q, k, v, ctx, lse, y_partial}, "mtf_mha_fwd buffer")) return rc;
-  return mha_fwd(d, x, w_q, w_k, w_v, w_o, scale, causal, q, k, v, ctx, lse, y_partial,
-                 static_cast<hipStream_t>(stream));
+  const int rc = mha_fwd(d, x, w_q, w_k, w_v, w_o, scale, causal, q, k, v, ctx, lse, single(y_partial),
+                         static_cast<hipStream_t>(stream));
+  return rc < 0 ? rc : MTF_OK;
 }
 
 size_t mtf_mha_bwd_workspace_bytes(const mtf_mha_dims* d) {
@@ -207,8 +278,9 @@ int mtf_mha_bwd(const mtf_mha_dims* d, const void* x, const void* w_q, const voi
     return rc;
   if (!workspace || workspace_bytes < mtf_mha_bwd_workspace_bytes(d) || !aligned16(workspace))
     return fail(MTF_ERR_WORKSPACE, "mtf_mha_bwd needs %zu bytes", mtf_mha_bwd_workspace_bytes(d));
-  return mha_bwd(d, x, w_q, w_k, w_v, w_o, q, k, v, ctx, lse, dy, scale, causal, dw_q, dw_k, dw_v, dw_o,
-                 dx_partial, mha_bwd_scratch(d, workspace), static_cast<hipStream_t>(stream));
+  const int rc = mha_bwd(d, x, w_q, w_k, w_v, w_o, q, k, v, ctx, lse, dy, scale, causal, dw_q, dw_k, dw_v, dw_o,
+                         single(dx_partial), mha_bwd_scratch(d, workspace), static_cast<hipStream_t>(stream));
+  return rc < 0 ? rc : MTF_OK;
 }
 
 static int check_layer(const mtf_layer_dims* d, mtf_ffn_dims* f, mtf_mha_dims* m) {
@@ -221,7 +293,7 @@ static int check_layer(const mtf_layer_dims* d, mtf_ffn_dims* f, mtf_mha_dims* m
 
 size_t mtf_layer_fwd_workspace_bytes(const mtf_layer_dims* d) {
   if (!d || d->batch <= 0 || d->length <= 0 || d->d_model <= 0) return 0;
-  return round256((size_t)d->batch * d->length * d->d_model * 4);  // one fp32 partial sum
+  return kLayerPartials * round256((size_t)d->batch * d->length * d->d_model * 4);  // fp32 partial sums
 }
 
 int mtf_layer_fwd(const mtf_layer_dims* d, const void* x, const mtf_layer_weights* w, float scale,
@@ -238,14 +310,17 @@ int mtf_layer_fwd(const mtf_layer_dims* d, const void* x, const mtf_layer_weight
     return fail(MTF_ERR_WORKSPACE, "mtf_layer_fwd needs %zu bytes", mtf_layer_fwd_workspace_bytes(d));
   hipStream_t s = static_cast<hipStream_t>(stream);
   const int64_t count = d->batch * d->length * d->d_model;
-  // u = x + R(MHA(x)); R = the Allreduce point, identity for a one-slice group
-  if (int rc = mha_fwd(&m, x, w->w_q, w->w_k, w->w_v, w->w_o, scale, causal, sv->q, sv->k, sv->v, sv->ctx,
-                       sv->lse, workspace, s))
-    return rc;
-  if (int rc = residual_add(workspace, x, sv->u, count, s)) return rc;
+  // u = x + R(MHA(x)); R = the Allreduce point.  For this one-slice group it degenerates to the
+  // sum of the k-range partial sums the einsum was cut into.
+  const Partials parts = carve(workspace, 2, count);
+  int n = mha_fwd(&m, x, w->w_q, w->w_k, w->w_v, w->w_o, scale, causal, sv->q, sv->k, sv->v, sv->ctx, sv->lse,
+                  parts, s);
+  if (n < 0) return n;
+  if (int rc = residual_add(parts, n, x, sv->u, count, s)) return rc;
   // z = u + R(FFN(u))
-  if (int rc = ffn_fwd(&f, sv->u, w->w_in, w->w_out, sv->a, workspace, s)) return rc;
-  return residual_add(workspace, sv->u, z, count, s);
+  n = ffn_fwd(&f, sv->u, w->w_in, w->w_out, sv->a, parts, s);
+  if (n < 0) return n;
+  return residual_add(parts, n, sv->u, z, count, s);
 }
 
 size_t mtf_layer_bwd_workspace_bytes(const mtf_layer_dims* d) {
@@ -255,7 +330,7 @@ size_t mtf_layer_bwd_workspace_bytes(const mtf_layer_dims* d) {
     return 0;
   f = mtf_ffn_dims{d->batch, d->length, d->d_model, d->d_ff};
   m = mtf_mha_dims{d->batch, d->length, d->d_model, d->heads, d->d_k};
-  const size_t partial = round256((size_t)d->batch * d->length * d->d_model * 4);
+  const size_t partial = kLayerPartials * round256((size_t)d->batch * d->length * d->d_model * 4);
   const size_t du = round256((size_t)d->batch * d->length * d->d_model * 2);
   return partial + du + std::max(mtf_ffn_bwd_workspace_bytes(&f), mtf_mha_bwd_workspace_bytes(&m));
 }
@@ -277,17 +352,18 @@ int mtf_layer_bwd(const mtf_layer_dims* d, const void* x, const mtf_layer_weight
   hipStream_t s = static_cast<hipStream_t>(stream);
   const int64_t count = d->batch * d->length * d->d_model;
   char* p = static_cast<char*>(workspace);
-  void* partial = p;
-  void* du = p + round256((size_t)count * 4);
-  void* rest = p + round256((size_t)count * 4) + round256((size_t)count * 2);
+  const size_t part_bytes = kLayerPartials * round256((size_t)count * 4);
+  void* du = p + part_bytes;
+  void* rest = p + part_bytes + round256((size_t)count * 2);
   // FFN sublayer: du = dz + R(dx_ffn_partial)
-  if (int rc = ffn_bwd(&f, sv->u, sv->a, w->w_in, w->w_out, dz, g->dw_in, g->dw_out, partial, rest, s)) return rc;
-  if (int rc = residual_add(partial, dz, du, count, s)) return rc;
+  int n = ffn_bwd(&f, sv->u, sv->a, w->w_in, w->w_out, dz, g->dw_in, g->dw_out, carve(p, 2, count), rest, s);
+  if (n < 0) return n;
+  if (int rc = residual_add(carve(p, 2, count), n, dz, du, count, s)) return rc;
   // attention sublayer: dx = du + R(dx_mha_partial)
-  if (int rc = mha_bwd(&m, x, w->w_q, w->w_k, w->w_v, w->w_o, sv->q, sv->k, sv->v, sv->ctx, sv->lse, du, scale,
-                       causal, g->dw_q, g->dw_k, g->dw_v, g->dw_o, partial, mha_bwd_scratch(&m, rest), s))
-    return rc;
-  return residual_add(partial, du, dx, count, s);
+  n = mha_bwd(&m, x, w->w_q, w->w_k, w->w_v, w->w_o, sv->q, sv->k, sv->v, sv->ctx, sv->lse, du, scale, causal,
+              g->dw_q, g->dw_k, g->dw_v, g->dw_o, carve(p, 3, count), mha_bwd_scratch(&m, rest), s);
+  if (n < 0) return n;
+  return residual_add(carve(p, 3, count), n, du, dx, count, s);
 }
 
 }  // extern "C"
