@@ -45,7 +45,7 @@ struct GemmDesc {
   };
   int nextra = 0;
   Extra extra[kMaxGroup - 1];
-  int tile = 0;  // 0 = choose by output size, 1 = 128x128 tiles, 2 = 256x256 tiles
+  int tile = 0;  // 0 = choose by output size, 1 = 128x128 tiles, 2 = 256x256 tiles, 3 = 128x128 with 4 stages
   // tuning aid: if set, workgroup 0 stores {shader-clock ticks, 100 MHz ticks} spent in the kernel
   uint64_t* debug_clocks = nullptr;
 };

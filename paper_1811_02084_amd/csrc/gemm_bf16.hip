@@ -38,17 +38,21 @@ namespace {
 
 constexpr int BK = 64;
 
-template <int BM_, int BN_, int WM_, int WN_, int GROUP_M_>
+template <int BM_, int BN_, int WM_, int WN_, int GROUP_M_, int STAGES_>
 struct TileCfg {
   static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_;
   static constexpr int kWaves = WM * WN, kThreads = kWaves * 64;
   static constexpr int TM = BM / WM / 32, TN = BN / WN / 32;  // 32x32 accumulators per wave
   static constexpr int kATile = BM * BK * 2, kBTile = BN * BK * 2, kStage = kATile + kBTile;  // bytes
   static constexpr int kGroupM = GROUP_M_;  // tile rows per L2 patch
+  static constexpr int kStages = STAGES_;   // k-tiles resident in LDS (one computing, the rest in flight)
+  static constexpr int kFragAhead = TM * TN >= 8 ? 1 : 2;  // k-steps of fragments fetched ahead
   static constexpr int kWavesPerSimd = 2;  // register budget: two wavefronts per SIMD
 };
-using LargeTile = TileCfg<256, 256, 2, 4, 4>;
-using SmallTile = TileCfg<128, 128, 2, 2, 8>;
+using LargeTile = TileCfg<256, 256, 2, 4, 4, 2>;      // 128 KiB LDS, one workgroup per CU
+using SmallTile = TileCfg<128, 128, 2, 2, 8, 2>;      // 64 KiB LDS, two workgroups per CU
+using SmallDeepTile = TileCfg<128, 128, 2, 2, 8, 4>;  // 128 KiB LDS: for outputs with at most one
+                                                      // small tile per CU, a longer load pipeline
 
 // Slot s of A/B/K is k-segment s of one problem (ngroup == 1) or, in a grouped launch, the
 // operands of problem s (then every problem has one segment and its own M, N, C and leading dims).
@@ -175,9 +179,9 @@ __device__ __forceinline__ bf16x8 read_fragment(const char* tile, int mn_base, i
 template <class Cfg, bool A_K, bool B_K, int EPI, bool OUT_BF16>
 __global__ void __launch_bounds__(Cfg::kThreads, Cfg::kWavesPerSimd) gemm_bf16_kernel(GemmArgs g) {
   constexpr int BM = Cfg::BM, BN = Cfg::BN, TM = Cfg::TM, TN = Cfg::TN;
-  // Two stages, used alternately by the twice-unrolled k loop below.
-  __shared__ __attribute__((aligned(1024))) char stage0[Cfg::kStage];
-  __shared__ __attribute__((aligned(1024))) char stage1[Cfg::kStage];
+  // Ring of kStages k-tiles: one being computed on, the others in flight.
+  constexpr int NS = Cfg::kStages;
+  __shared__ __attribute__((aligned(1024))) char ring[NS * Cfg::kStage];
 
   const uint64_t t_start = g.debug_clocks ? clock64() : 0, w_start = g.debug_clocks ? wall_clock64() : 0;
   // ---- which tile: XCD-aware remap, then patches of kGroupM tile rows
@@ -212,15 +216,6 @@ __global__ void __launch_bounds__(Cfg::kThreads, Cfg::kWavesPerSimd) gemm_bf16_k
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-  // k-tiles of all segments, in order
-  int tiles_in_seg[kMaxSegments];
-  int total_tiles = 0;
-#pragma unroll
-  for (int s = 0; s < kMaxSegments; ++s) {
-    tiles_in_seg[s] = s < g.nseg ? (g.K[grp + s] + BK - 1) / BK : 0;  // grp > 0 only with nseg == 1
-    total_tiles += tiles_in_seg[s];
-  }
-
   TileLoader<A_K, BM, Cfg::kWaves> load_a;
   TileLoader<B_K, BN, Cfg::kWaves> load_b;
   load_a.init(lda, m0, M, wave, lane);
@@ -228,43 +223,70 @@ __global__ void __launch_bounds__(Cfg::kThreads, Cfg::kWavesPerSimd) gemm_bf16_k
   const int64_t a_tile0 = A_K ? (int64_t)m0 * lda : m0, a_kstep = A_K ? 1 : lda;
   const int64_t b_tile0 = B_K ? (int64_t)n0 * ldb : n0, b_kstep = B_K ? 1 : ldb;
 
-  auto issue = [&](int kt, char* st) {
-    int s = 0, local = kt;
+  // k-tiles of all segments, in order.  Everything the per-tile issue needs is brought into
+  // scalar registers once (indexing the kernel arguments inside the loop costs a scalar memory
+  // load and a wait per k-tile) and then advanced incrementally.
+  const char* seg_a[kMaxSegments];
+  const char* seg_b[kMaxSegments];
+  int seg_k[kMaxSegments];
+  int total_tiles = 0;
+#pragma unroll
+  for (int s = 0; s < kMaxSegments; ++s) {
+    const int slot = min(grp + s, kMaxGroup - 1);  // grp > 0 only with nseg == 1
+    seg_a[s] = reinterpret_cast<const char*>(g.A[slot] + offA + a_tile0);
+    seg_b[s] = reinterpret_cast<const char*>(g.B[slot] + offB + b_tile0);
+    seg_k[s] = s < g.nseg ? g.K[slot] : 0;
+    total_tiles += (seg_k[s] + BK - 1) / BK;
+  }
+  const int64_t a_tile_bytes = a_kstep * (BK * 2), b_tile_bytes = b_kstep * (BK * 2);
+  const char *next_a = seg_a[0], *next_b = seg_b[0];  // operand origins of the next tile to issue
+  int next_seg = 0, next_left = seg_k[0];             // its segment and the k still ahead in it
+  uint32_t full_hist = 0;                             // bit i: the (i+1)-th latest issued tile was full
+
+  auto issue_next = [&](char* st) {
+    // skip exhausted (or empty) segments
 #pragma unroll
     for (int q = 0; q < kMaxSegments - 1; ++q)
-      if (s == q && local >= tiles_in_seg[q]) {
-        local -= tiles_in_seg[q];
-        s = q + 1;
+      if (next_left <= 0 && next_seg == q) {
+        next_seg = q + 1;
+        next_a = seg_a[q + 1];
+        next_b = seg_b[q + 1];
+        next_left = seg_k[q + 1];
       }
-    const int k0 = local * BK;
-    s += grp;
-    const bf16_t* pa = g.A[s] + offA + a_tile0 + k0 * a_kstep;
-    const bf16_t* pb = g.B[s] + offB + b_tile0 + k0 * b_kstep;
-    load_a.issue(reinterpret_cast<const char*>(pa), st, wave, lane, g.K[s] - k0);
-    load_b.issue(reinterpret_cast<const char*>(pb), st + Cfg::kATile, wave, lane, g.K[s] - k0);
+    load_a.issue(next_a, st, wave, lane, next_left);
+    load_b.issue(next_b, st + Cfg::kATile, wave, lane, next_left);
+    full_hist = (full_hist << 1) | (next_left >= BK ? 1u : 0u);
+    next_a += a_tile_bytes;
+    next_b += b_tile_bytes;
+    next_left -= BK;
   };
-  // One k-tile = 4 steps of 16.  The fragments of step ks+1 are read from LDS while the MFMAs of
-  // step ks run: one LDS read is slotted in front of each of the first TM+TN MFMAs of a step.
+  // One k-tile = 4 steps of 16.  LDS->register latency is several hundred cycles, more than the
+  // MFMAs of one step take, so fragments are fetched kAhead steps ahead into a rotating set of
+  // kAhead+1 register buffers: one LDS read is slotted in front of each of the first TM+TN MFMAs
+  // of a step.
+  constexpr int kAhead = Cfg::kFragAhead;
+  auto fetch = [&](const char* st, int ks, bf16x8* a_dst, bf16x8* b_dst, int which) {
+    // which: 0..TN-1 -> B fragment, TN..TN+TM-1 -> A fragment
+    if (which < TN)
+      b_dst[which] = read_fragment<B_K, BN>(st + Cfg::kATile, wave_n + which * 32, ks, lane);
+    else
+      a_dst[which - TN] = read_fragment<A_K, BM>(st, wave_m + (which - TN) * 32, ks, lane);
+  };
   auto compute = [&](const char* st) {
-    bf16x8 af[2][TM], bf[2][TN];
+    bf16x8 af[kAhead + 1][TM], bf[kAhead + 1][TN];
 #pragma unroll
-    for (int j = 0; j < TN; ++j) bf[0][j] = read_fragment<B_K, BN>(st + Cfg::kATile, wave_n + j * 32, 0, lane);
+    for (int p = 0; p < kAhead; ++p)
 #pragma unroll
-    for (int i = 0; i < TM; ++i) af[0][i] = read_fragment<A_K, BM>(st, wave_m + i * 32, 0, lane);
+      for (int w = 0; w < TM + TN; ++w) fetch(st, p, af[p], bf[p], w);
 #pragma unroll
     for (int ks = 0; ks < BK / 16; ++ks) {
-      const int cur = ks & 1, nxt = cur ^ 1;
+      const int cur = ks % (kAhead + 1), nxt = (ks + kAhead) % (kAhead + 1);
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
           const int slot = i * TN + j;  // MFMA number within the step
-          if (ks + 1 < BK / 16) {
-            if (slot < TN)
-              bf[nxt][slot] = read_fragment<B_K, BN>(st + Cfg::kATile, wave_n + slot * 32, ks + 1, lane);
-            else if (slot < TN + TM)
-              af[nxt][slot - TN] = read_fragment<A_K, BM>(st, wave_m + (slot - TN) * 32, ks + 1, lane);
-          }
+          if (ks + kAhead < BK / 16 && slot < TM + TN) fetch(st, ks + kAhead, af[nxt], bf[nxt], slot);
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[cur][j], af[cur][i], acc[i][j], 0, 0, 0);
           // keep this read-then-MFMA order: left alone, the scheduler sinks every read to just
           // before its first use (fewer live registers) and the overlap is lost
@@ -272,22 +294,34 @@ __global__ void __launch_bounds__(Cfg::kThreads, Cfg::kWavesPerSimd) gemm_bf16_k
         }
     }
   };
-  // Wait for this wave's loads of the tile about to be used, then for everybody's; passing the
-  // barrier also means nobody still reads the other stage, which the next issue() overwrites.
-  auto tile_ready = [&]() {
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  // Loads complete in issue order, so "tile kt has landed" = at most the loads of the newer tiles
+  // are still outstanding.  A ragged tile may issue fewer than the usual number of loads per wave,
+  // so only full newer tiles are counted (a smaller allowance only waits longer).
+  constexpr int kLoadsPerTile = TileLoader<A_K, BM, Cfg::kWaves>::NL + TileLoader<B_K, BN, Cfg::kWaves>::NL;
+  auto wait_for_tile = [&](int kt) {
+    const int newer = min(NS - 2, total_tiles - 1 - kt);  // tiles issued after tile kt
+    const int allowed = newer > 0 ? __builtin_popcount(full_hist & ((1u << newer) - 1u)) : 0;
+    if (NS >= 4 && allowed >= 2)
+      asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * kLoadsPerTile) : "memory");
+    else if (NS >= 3 && allowed >= 1)
+      asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kLoadsPerTile) : "memory");
+    else
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    // passing the barrier also means everyone finished computing on tile kt-1, whose stage the
+    // next issue overwrites
     __syncthreads();
   };
 
-  if (total_tiles > 0) issue(0, stage0);
-  for (int kt = 0; kt < total_tiles; kt += 2) {
-    tile_ready();
-    if (kt + 1 < total_tiles) issue(kt + 1, stage1);
-    compute(stage0);
-    if (kt + 1 >= total_tiles) break;
-    tile_ready();
-    if (kt + 2 < total_tiles) issue(kt + 2, stage0);
-    compute(stage1);
+#pragma unroll
+  for (int p = 0; p < NS - 1; ++p)
+    if (p < total_tiles) issue_next(ring + p * Cfg::kStage);
+  int stage = 0, fill = NS - 1;  // stage of tile kt; stage that tile kt+NS-1 goes to
+  for (int kt = 0; kt < total_tiles; ++kt) {
+    wait_for_tile(kt);
+    if (kt + NS - 1 < total_tiles) issue_next(ring + fill * Cfg::kStage);
+    compute(ring + stage * Cfg::kStage);
+    stage = stage + 1 == NS ? 0 : stage + 1;
+    fill = fill + 1 == NS ? 0 : fill + 1;
   }
 
   if (g.debug_clocks && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) {
@@ -344,15 +378,20 @@ __global__ void __launch_bounds__(Cfg::kThreads, Cfg::kWavesPerSimd) gemm_bf16_k
       }
     }
   }
+  if (g.debug_clocks && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // stores issued by this wave have been accepted
+    g.debug_clocks[2] = clock64() - t_start;
+    g.debug_clocks[3] = wall_clock64() - w_start;
+  }
 }
 
 template <class Cfg, bool A_K, bool B_K, int EPI, bool OUT_BF16>
 int launch_instance(const GemmArgs& a, int batch, hipStream_t stream) {
   // name as a profiler prints the instantiation
-  static char name[96] = "";
+  static char name[96] = "";  // fits mtf_kernel_time::kernel
   if (!name[0])
-    std::snprintf(name, sizeof name, "gemm_bf16_kernel<TileCfg<%d, %d, %d, %d, %d>, %s, %s, %d, %s>", Cfg::BM,
-                  Cfg::BN, Cfg::WM, Cfg::WN, Cfg::kGroupM, A_K ? "true" : "false", B_K ? "true" : "false", EPI,
+    std::snprintf(name, sizeof name, "gemm_bf16_kernel<TileCfg<%d, %d, %d, %d, %d, %d>, %s, %s, %d, %s>", Cfg::BM,
+                  Cfg::BN, Cfg::WM, Cfg::WN, Cfg::kGroupM, Cfg::kStages, A_K ? "true" : "false", B_K ? "true" : "false", EPI,
                   OUT_BF16 ? "true" : "false");
   GemmArgs args = a;
   int64_t tiles = 0;
@@ -469,8 +508,10 @@ int gemm_bf16_launch(const GemmDesc& d, hipStream_t stream) {
   const double cost_large = (double)ceil_div(large_tiles, 256) * 4.0;
   const double cost_small = (double)ceil_div(small_tiles, 512) * 2.0 / 0.8;
   int tile = d.tile;
-  if (tile == 0) tile = cost_large <= cost_small ? 2 : 1;
-  return tile == 2 ? launch_cfg<LargeTile>(d, a, batch, stream) : launch_cfg<SmallTile>(d, a, batch, stream);
+  if (tile == 0) tile = cost_large <= cost_small ? 2 : (small_tiles <= 256 ? 3 : 1);
+  if (tile == 2) return launch_cfg<LargeTile>(d, a, batch, stream);
+  if (tile == 3) return launch_cfg<SmallDeepTile>(d, a, batch, stream);
+  return launch_cfg<SmallTile>(d, a, batch, stream);
 }
 
 }  // namespace mtf
