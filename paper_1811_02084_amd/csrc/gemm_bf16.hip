@@ -47,6 +47,10 @@ struct TileCfg {
   static constexpr int kGroupM = GROUP_M_;  // tile rows per L2 patch
   static constexpr int kStages = STAGES_;   // k-tiles resident in LDS (one computing, the rest in flight)
   static constexpr int kFragAhead = TM * TN >= 8 ? 1 : 2;  // k-steps of fragments fetched ahead
+  // Where in a k-tile the loads of the next one are issued: after the first step's MFMAs (keeps
+  // the matrix cores fed across the tile boundary; pays off when a step has many MFMAs) or
+  // right after the barrier.
+  static constexpr bool kLateIssue = false;  // measured: no consistent gain at either tile shape
   static constexpr int kWavesPerSimd = 2;  // register budget: two wavefronts per SIMD
 };
 using LargeTile = TileCfg<256, 256, 2, 4, 4, 2>;      // 128 KiB LDS, one workgroup per CU
@@ -272,8 +276,11 @@ __global__ void __launch_bounds__(Cfg::kThreads, Cfg::kWavesPerSimd) gemm_bf16_k
     else
       a_dst[which - TN] = read_fragment<A_K, BM>(st, wave_m + (which - TN) * 32, ks, lane);
   };
-  auto compute = [&](const char* st) {
+  // `next_stage` (or nullptr): where to start loading the next k-tile; done after the first
+  // step's MFMAs are under way, so the matrix cores are not kept waiting for the load issue.
+  auto compute = [&](const char* st, char* next_stage) {
     bf16x8 af[kAhead + 1][TM], bf[kAhead + 1][TN];
+    if (!Cfg::kLateIssue && next_stage) issue_next(next_stage);
 #pragma unroll
     for (int p = 0; p < kAhead; ++p)
 #pragma unroll
@@ -292,6 +299,10 @@ __global__ void __launch_bounds__(Cfg::kThreads, Cfg::kWavesPerSimd) gemm_bf16_k
           // before its first use (fewer live registers) and the overlap is lost
           __builtin_amdgcn_sched_barrier(0);
         }
+      if (Cfg::kLateIssue && ks == 0 && next_stage) {
+        issue_next(next_stage);
+        __builtin_amdgcn_sched_barrier(0);
+      }
     }
   };
   // Loads complete in issue order, so "tile kt has landed" = at most the loads of the newer tiles
@@ -318,8 +329,7 @@ __global__ void __launch_bounds__(Cfg::kThreads, Cfg::kWavesPerSimd) gemm_bf16_k
   int stage = 0, fill = NS - 1;  // stage of tile kt; stage that tile kt+NS-1 goes to
   for (int kt = 0; kt < total_tiles; ++kt) {
     wait_for_tile(kt);
-    if (kt + NS - 1 < total_tiles) issue_next(ring + fill * Cfg::kStage);
-    compute(ring + stage * Cfg::kStage);
+    compute(ring + stage * Cfg::kStage, kt + NS - 1 < total_tiles ? ring + fill * Cfg::kStage : nullptr);
     stage = stage + 1 == NS ? 0 : stage + 1;
     fill = fill + 1 == NS ? 0 : fill + 1;
   }
