@@ -15,7 +15,8 @@
 //     an m/n-contiguous operand is read with ds_read_b64_tr_b16, the LDS transpose load, so no
 //     operand is ever transposed in memory or registers;
 //   * the MFMA is issued with its operands exchanged (B-fragment as the instruction's A), which
-//     leaves every lane holding 4 consecutive n of one row m: 16-byte fp32 / 8-byte bf16 stores;
+//     leaves every lane holding 4 consecutive n of one row m; the epilogue transposes 32x64 slabs
+//     through LDS so that global stores (and aux / old-C loads) are contiguous 256 B row pieces;
 //   * out-of-range chunks (ragged M, N, K) are fetched from a 16-byte block of zeros instead;
 //   * workgroup ids are dealt round-robin to the 8 XCDs by hardware, so ids are remapped to make
 //     each XCD (own L2) work on a compact patch of C.
@@ -31,6 +32,7 @@ typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(4 * sizeof(short)))) short s16x4;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
 
 #define LDS_PTR(T, p) ((__attribute__((address_space(3))) T*)(p))
 
@@ -338,55 +340,71 @@ __global__ void __launch_bounds__(Cfg::kThreads, Cfg::kWavesPerSimd) gemm_bf16_k
     g.debug_clocks[0] = clock64() - t_start;
     g.debug_clocks[1] = wall_clock64() - w_start;
   }
-  // ---- epilogue: lane holds row m = .. + lane%32 and, per group q, 4 consecutive n
+  // ---- epilogue.  A lane holds, per accumulator, one row m and 4 x 4 consecutive n: stored
+  // directly that would be 16-byte pieces scattered over 32 rows per instruction.  Instead each
+  // wave passes its 32 x 64 accumulator slabs through a private LDS area (the operand ring is
+  // free now) and reads them back row-wise, so every global access is 16 lanes x 16 B = one
+  // contiguous 256 B row segment; aux / old-C reads of the fused epilogues get the same shape.
+  static_assert(TN == 2, "epilogue staging assumes 64-column wave tiles");
+  constexpr int kPitch = 64 * 4 + 16;  // fp32 row + 16 B: row-to-row bank shift of 4
+  __syncthreads();                     // everyone is done reading the last k-tile
+  char* slab = ring + wave * (32 * kPitch);
   const int lane_m = lane & 31, lane_h = lane >> 5;
+  const int out_row = lane >> 4, out_col = (lane & 15) * 4;  // read-back: 4 rows per instruction
   void* const Cg = g.C[grp];
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
-    const int m = m0 + wave_m + i * 32 + lane_m;
-    if (m >= M) continue;
 #pragma unroll
-    for (int j = 0; j < TN; ++j) {
+    for (int j = 0; j < TN; ++j)
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
-        const int n = n0 + wave_n + j * 32 + q * 8 + lane_h * 4;
-        if (n >= N) continue;
-        const int64_t idx = offC + (int64_t)m * ldc + n;
-        float v[4];
+        f32x4 v;
 #pragma unroll
         for (int e = 0; e < 4; ++e) v[e] = g.alpha * acc[i][j][q * 4 + e];
-        if (g.accumulate) {
-          if (OUT_BF16) {
-            uint2 old = *reinterpret_cast<const uint2*>(static_cast<const bf16_t*>(Cg) + idx);
-            v[0] += __uint_as_float(old.x << 16);
-            v[1] += __uint_as_float(old.x & 0xffff0000u);
-            v[2] += __uint_as_float(old.y << 16);
-            v[3] += __uint_as_float(old.y & 0xffff0000u);
-          } else {
-            float4 old = *reinterpret_cast<const float4*>(static_cast<const float*>(Cg) + idx);
-            v[0] += old.x;
-            v[1] += old.y;
-            v[2] += old.z;
-            v[3] += old.w;
-          }
-        }
-        if (EPI == MTF_EPI_RELU) {
-#pragma unroll
-          for (int e = 0; e < 4; ++e) v[e] = fmaxf(v[e], 0.f);
-        } else if (EPI == MTF_EPI_MASK_GT0) {
-          uint2 a = *reinterpret_cast<const uint2*>(g.aux + idx);
-          // bf16 > 0  <=>  sign bit clear and magnitude non-zero
-          const uint32_t w[4] = {a.x & 0xffffu, a.x >> 16, a.y & 0xffffu, a.y >> 16};
-#pragma unroll
-          for (int e = 0; e < 4; ++e) v[e] = (w[e] != 0u && w[e] < 0x8000u) ? v[e] : 0.f;
-        }
-        if (OUT_BF16)
-          *reinterpret_cast<uint2*>(static_cast<bf16_t*>(Cg) + idx) =
-              make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
-        else
-          *reinterpret_cast<float4*>(static_cast<float*>(Cg) + idx) = make_float4(v[0], v[1], v[2], v[3]);
+        *LDS_PTR(f32x4, slab + lane_m * kPitch + (j * 32 + q * 8 + lane_h * 4) * 4) = v;
       }
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int it = 0; it < 8; ++it) {
+      const int r = it * 4 + out_row;
+      const f32x4 t = *LDS_PTR(const f32x4, slab + r * kPitch + out_col * 4);
+      const int m = m0 + wave_m + i * 32 + r;
+      const int n = n0 + wave_n + out_col;
+      if (m >= M || n >= N) continue;
+      const int64_t idx = offC + (int64_t)m * ldc + n;
+      float v[4] = {t[0], t[1], t[2], t[3]};
+      if (g.accumulate) {
+        if (OUT_BF16) {
+          uint2 old = *reinterpret_cast<const uint2*>(static_cast<const bf16_t*>(Cg) + idx);
+          v[0] += __uint_as_float(old.x << 16);
+          v[1] += __uint_as_float(old.x & 0xffff0000u);
+          v[2] += __uint_as_float(old.y << 16);
+          v[3] += __uint_as_float(old.y & 0xffff0000u);
+        } else {
+          float4 old = *reinterpret_cast<const float4*>(static_cast<const float*>(Cg) + idx);
+          v[0] += old.x;
+          v[1] += old.y;
+          v[2] += old.z;
+          v[3] += old.w;
+        }
+      }
+      if (EPI == MTF_EPI_RELU) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = fmaxf(v[e], 0.f);
+      } else if (EPI == MTF_EPI_MASK_GT0) {
+        uint2 a = *reinterpret_cast<const uint2*>(g.aux + idx);
+        // bf16 > 0  <=>  sign bit clear and magnitude non-zero
+        const uint32_t w[4] = {a.x & 0xffffu, a.x >> 16, a.y & 0xffffu, a.y >> 16};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = (w[e] != 0u && w[e] < 0x8000u) ? v[e] : 0.f;
+      }
+      if (OUT_BF16)
+        *reinterpret_cast<uint2*>(static_cast<bf16_t*>(Cg) + idx) =
+            make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
+      else
+        *reinterpret_cast<float4*>(static_cast<float*>(Cg) + idx) = make_float4(v[0], v[1], v[2], v[3]);
     }
+    __builtin_amdgcn_wave_barrier();
   }
   if (g.debug_clocks && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) {
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // stores issued by this wave have been accepted
