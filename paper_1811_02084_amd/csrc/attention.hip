@@ -185,7 +185,8 @@ __global__ void __launch_bounds__(NWAVES * 64, 2) attn_fwd_kernel(AttnArgs a) {
 #pragma unroll
   for (int i = 0; i < 4; ++i) o[i] = zero16();
   float m2 = -INFINITY, lsum = 0.f;  // running max (log2 units) and row sum
-  const float c2 = a.scale * kLog2e;
+  const float c2 = fabsf(a.scale) * kLog2e;
+  const bool negate = a.scale < 0.f;  // max(s * c) needs c >= 0: use (-s) * |c| instead
 
   const int kv_end = a.causal ? min(L, q0 + NWAVES * 32) : L;
   const int n_tiles = (kv_end + kTileRows - 1) / kTileRows;
@@ -207,20 +208,46 @@ __global__ void __launch_bounds__(NWAVES * 64, 2) attn_fwd_kernel(AttnArgs a) {
         s[kvb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rows_frag(kt_, kvb * 32, ks, lane), qf[ks],
                                                          s[kvb], 0, 0, 0);
     }
+    if (negate) {
+#pragma unroll
+      for (int kvb = 0; kvb < 2; ++kvb)
+#pragma unroll
+        for (int jj = 0; jj < 16; ++jj) s[kvb][jj] = -s[kvb][jj];
+    }
+    // Softmax bookkeeping, kept cheap on the vector ALU (it competes with the matrix cores):
+    //  * masking only on tiles that can contain a hidden position for this wave (wave-uniform);
+    //  * the scale is folded into one fma per logit: p = exp2(s * c2 - m);
+    //  * the running maximum m2 is only raised (and O, lsum rescaled) when some row's maximum
+    //    exceeds it by more than kSlack: until then p <= 2^kSlack, harmless in fp32 / bf16.
+    const bool need_mask = kv0 + kTileRows > L || (a.causal && kv0 + kTileRows - 1 > q0 + wave * 32);
+    if (need_mask) {
+#pragma unroll
+      for (int kvb = 0; kvb < 2; ++kvb)
+#pragma unroll
+        for (int jj = 0; jj < 16; ++jj) {
+          const int kv = kv0 + kvb * 32 + acc_row(jj, hf);
+          const bool vis = kv < L && (!a.causal || kv <= q_lane);
+          s[kvb][jj] = vis ? s[kvb][jj] : -INFINITY;
+        }
+    }
     float mx = -INFINITY;
 #pragma unroll
     for (int kvb = 0; kvb < 2; ++kvb)
 #pragma unroll
-      for (int jj = 0; jj < 16; ++jj) {
-        const int kv = kv0 + kvb * 32 + acc_row(jj, hf);
-        const bool vis = kv < L && (!a.causal || kv <= q_lane);
-        const float x = vis ? s[kvb][jj] * c2 : -INFINITY;
-        s[kvb][jj] = x;
-        mx = fmaxf(mx, x);
-      }
+      for (int jj = 0; jj < 16; ++jj) mx = fmaxf(mx, s[kvb][jj]);
     mx = fmaxf(mx, __shfl_xor(mx, 32));  // the other half-wave holds the rest of this query's row
-    const float m_new = fmaxf(m2, mx);   // finite: tile 0 always shows position 0
-    const float alpha = __builtin_amdgcn_exp2f(m2 - m_new);
+    mx = mx == -INFINITY ? mx : mx * c2;  // c2 >= 0 (logits were negated for a negative scale)
+    constexpr float kSlack = 8.f;
+    if (__any(mx > m2 + kSlack)) {  // first tile: m2 = -inf, always taken; position 0 is visible
+      const float m_new = fmaxf(m2, mx);
+      const float alpha = __builtin_amdgcn_exp2f(m2 - m_new);
+      lsum *= alpha;
+      m2 = m_new;
+#pragma unroll
+      for (int blk = 0; blk < 4; ++blk)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) o[blk][e] *= alpha;
+    }
     float psum = 0.f;
     bf16x8 pf[4];
 #pragma unroll
@@ -228,24 +255,22 @@ __global__ void __launch_bounds__(NWAVES * 64, 2) attn_fwd_kernel(AttnArgs a) {
       float p[16];
 #pragma unroll
       for (int jj = 0; jj < 16; ++jj) {
-        p[jj] = __builtin_amdgcn_exp2f(s[kvb][jj] - m_new);  // exp2(-inf) = 0 for hidden positions
-        psum += p[jj];
+        float pe = __builtin_amdgcn_exp2f(fmaf(s[kvb][jj], c2, -m2));
+        if (need_mask) pe = s[kvb][jj] == -INFINITY ? 0.f : pe;  // also covers c2 == 0 (0 * inf)
+        p[jj] = pe;
+        psum += pe;
       }
       pf[kvb * 2 + 0] = pack8(p);
       pf[kvb * 2 + 1] = pack8(p + 8);
     }
     psum += __shfl_xor(psum, 32);
-    lsum = lsum * alpha + psum;
-    m2 = m_new;
+    lsum += psum;
 #pragma unroll
-    for (int blk = 0; blk < 4; ++blk) {
-#pragma unroll
-      for (int e = 0; e < 16; ++e) o[blk][e] *= alpha;
+    for (int blk = 0; blk < 4; ++blk)
 #pragma unroll
       for (int t = 0; t < 4; ++t)
         o[blk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cols_frag(vt_, blk * 32, t * 16, lane), pf[t],
                                                          o[blk], 0, 0, 0);
-    }
   };
   // Two stages: the tile after the one being processed is in flight.  Passing the barrier means
   // everyone has the current tile and is done with the stage the next issue() overwrites.
@@ -316,7 +341,7 @@ __global__ void __launch_bounds__(NWAVES * 64, 2) attn_dq_kernel(AttnArgs a) {
     dof[ks] = global_rows_frag(dob, rs, q_load, ks, lane);
   }
   const int64_t stat = ((int64_t)b * H + h) * L + q_load;
-  const float lse2 = a.lse_in[stat] * kLog2e, dl = a.delta_in[stat];
+  const float lse2 = a.lse_in[stat] * kLog2e, dls = a.delta_in[stat] * a.scale;
   const float c2 = a.scale * kLog2e;
 
   f32x16 dq[4];
@@ -343,12 +368,16 @@ __global__ void __launch_bounds__(NWAVES * 64, 2) attn_dq_kernel(AttnArgs a) {
         dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rows_frag(vt_, kvb * 32, ks, lane), dof[ks], dp, 0, 0, 0);
       }
       float ds[16];
+      const bool need_mask = kv0 + kTileRows > L || (a.causal && kv0 + kTileRows - 1 > q0 + wave * 32);
 #pragma unroll
       for (int jj = 0; jj < 16; ++jj) {
-        const int kv = kv0 + kvb * 32 + acc_row(jj, hf);
-        const bool vis = kv < L && (!a.causal || kv <= q_lane);
-        const float p = __builtin_amdgcn_exp2f(s[jj] * c2 - lse2);
-        ds[jj] = vis ? p * (dp[jj] - dl) * a.scale : 0.f;
+        const float p = __builtin_amdgcn_exp2f(fmaf(s[jj], c2, -lse2));
+        ds[jj] = p * fmaf(dp[jj], a.scale, -dls);  // p * (dp - delta) * scale
+        if (need_mask) {
+          const int kv = kv0 + kvb * 32 + acc_row(jj, hf);
+          const bool vis = kv < L && (!a.causal || kv <= q_lane);
+          ds[jj] = vis ? ds[jj] : 0.f;
+        }
       }
       dsf[kvb * 2 + 0] = pack8(ds);
       dsf[kvb * 2 + 1] = pack8(ds + 8);
@@ -416,7 +445,7 @@ __global__ void __launch_bounds__(NWAVES * 64, 1) attn_dkv_kernel(AttnArgs a) {
     if (threadIdx.x < kTileRows) {
       const int qi = min(q0 + (int)threadIdx.x, L - 1);
       stats[threadIdx.x] = lse_row[qi] * kLog2e;
-      stats[kTileRows + threadIdx.x] = delta_row[qi];
+      stats[kTileRows + threadIdx.x] = delta_row[qi] * a.scale;
     }
   };
   auto process = [&](int t, const char* st, const float* stats) {
@@ -434,19 +463,27 @@ __global__ void __launch_bounds__(NWAVES * 64, 1) attn_dkv_kernel(AttnArgs a) {
         dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rows_frag(dot_, qblk * 32, ks, lane), vf[ks], dp, 0, 0, 0);
       }
       float p[16], ds[16];
+      // a hidden (query, memory) pair can only occur on ragged or diagonal tiles (wave-uniform)
+      const bool need_mask = q0 + kTileRows > L || kvblk0 + wave * 32 + 32 > L ||
+                             (a.causal && kvblk0 + wave * 32 + 31 > q0);
 #pragma unroll
       for (int g4 = 0; g4 < 4; ++g4) {
         const int r0 = qblk * 32 + g4 * 8 + hf * 4;  // 4 consecutive query rows of this group
         const f32x4 l4 = *LDS_PTR(const f32x4, reinterpret_cast<const char*>(lset_) + r0 * 4);
-        const f32x4 d4 = *LDS_PTR(const f32x4, reinterpret_cast<const char*>(delt_) + r0 * 4);
+        const f32x4 d4 = *LDS_PTR(const f32x4, reinterpret_cast<const char*>(delt_) + r0 * 4);  // delta * scale
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const int jj = g4 * 4 + e;
-          const int qi = q0 + r0 + e;
-          const bool vis = qi < L && kv_lane < L && (!a.causal || kv_lane <= qi);
-          const float pe = vis ? __builtin_amdgcn_exp2f(s[jj] * c2 - l4[e]) : 0.f;
+          float pe = __builtin_amdgcn_exp2f(fmaf(s[jj], c2, -l4[e]));
+          float de = pe * fmaf(dp[jj], a.scale, -d4[e]);  // p * (dp - delta) * scale
+          if (need_mask) {
+            const int qi = q0 + r0 + e;
+            const bool vis = qi < L && kv_lane < L && (!a.causal || kv_lane <= qi);
+            pe = vis ? pe : 0.f;
+            de = vis ? de : 0.f;
+          }
           p[jj] = pe;
-          ds[jj] = vis ? pe * (dp[jj] - d4[e]) * a.scale : 0.f;
+          ds[jj] = de;
         }
       }
       pf[qblk * 2 + 0] = pack8(p);
@@ -499,9 +536,12 @@ AttnArgs make_args(const AttnShape& s) {
 
 }  // namespace
 
-// Query (or memory) rows per workgroup: 128 when that still gives every CU a workgroup, else 64.
-static int waves_per_group(const AttnShape& s) {
-  return ceil_div(s.length, 128) * s.heads * s.batch >= 256 ? 4 : 2;
+// Query (or memory) rows per workgroup: as many as still give every CU a workgroup (more rows
+// share each K/V tile that is loaded); `max_waves` caps it for the register-hungry kernel.
+static int waves_per_group(const AttnShape& s, int max_waves) {
+  for (int nw = max_waves; nw > 2; nw /= 2)
+    if (ceil_div(s.length, nw * 32) * s.heads * s.batch >= 256) return nw;
+  return 2;
 }
 
 int attn_fwd_launch(const AttnShape& s, const bf16_t* q, const bf16_t* k, const bf16_t* v,
@@ -513,9 +553,12 @@ int attn_fwd_launch(const AttnShape& s, const bf16_t* q, const bf16_t* k, const 
   const double pairs = s.causal ? 0.5 * s.length * (s.length + 1.0) : (double)s.length * s.length;
   const double flops = 2.0 * 2.0 * s.batch * s.heads * pairs * kHeadDim;
   const double bytes = 4.0 * s.batch * s.length * s.heads * kRowBytes;
-  const int nw = waves_per_group(s);
+  const int nw = waves_per_group(s, 8);
   dim3 grid((unsigned)ceil_div(s.length, nw * 32), (unsigned)s.heads, (unsigned)s.batch);
-  if (nw == 4) {
+  if (nw == 8) {
+    LaunchTimer timer("attn_fwd_kernel<8>", flops, bytes, stream);
+    attn_fwd_kernel<8><<<grid, 512, 0, stream>>>(a);
+  } else if (nw == 4) {
     LaunchTimer timer("attn_fwd_kernel<4>", flops, bytes, stream);
     attn_fwd_kernel<4><<<grid, 256, 0, stream>>>(a);
   } else {
@@ -540,17 +583,22 @@ int attn_bwd_launch(const AttnShape& s, const bf16_t* q, const bf16_t* k, const 
   if (int rc = launch_status("attn_delta_kernel")) return rc;
   AttnArgs a = make_args(s);
   a.q = q; a.k = k; a.v = v; a.dctx = dctx; a.lse_in = lse; a.delta_in = delta;
-  const int nw = waves_per_group(s);
-  dim3 grid((unsigned)ceil_div(s.length, nw * 32), (unsigned)s.heads, (unsigned)s.batch);
-  a.out0 = dq;
   {  // dq = einsum(ds, k): 1 of the 4 backward contractions (the recomputed logits and dp are overhead here)
-    LaunchTimer timer(nw == 4 ? "attn_dq_kernel<4>" : "attn_dq_kernel<2>", unit, 5.0 * act, stream);
-    if (nw == 4)
+    const int nw = waves_per_group(s, 8);
+    dim3 grid((unsigned)ceil_div(s.length, nw * 32), (unsigned)s.heads, (unsigned)s.batch);
+    a.out0 = dq;
+    LaunchTimer timer(nw == 8 ? "attn_dq_kernel<8>" : nw == 4 ? "attn_dq_kernel<4>" : "attn_dq_kernel<2>", unit,
+                      5.0 * act, stream);
+    if (nw == 8)
+      attn_dq_kernel<8><<<grid, 512, 0, stream>>>(a);
+    else if (nw == 4)
       attn_dq_kernel<4><<<grid, 256, 0, stream>>>(a);
     else
       attn_dq_kernel<2><<<grid, 128, 0, stream>>>(a);
   }
   if (int rc = launch_status("attn_dq_kernel")) return rc;
+  const int nw = waves_per_group(s, 4);
+  dim3 grid((unsigned)ceil_div(s.length, nw * 32), (unsigned)s.heads, (unsigned)s.batch);
   a.out0 = dk;
   a.out1 = dv;
   {  // dp, dv, dk: 3 of the 4 backward contractions
