@@ -61,9 +61,21 @@ __device__ __forceinline__ void load16_to_lds(const char* uniform_base, uint32_t
       : "memory", "m0");
 }
 
+__device__ __forceinline__ void wait_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
 __device__ __forceinline__ void wait_loads_then_barrier() {
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  wait_loads();
   __syncthreads();
+}
+
+// The compiler's bookkeeping of outstanding loads does not see the asm tile loads.  A value it
+// loaded itself and first uses inside the tile loop would get its s_waitcnt vmcnt(n) there, on
+// every trip, and that wait also drains the asynchronous loads of the next tile - the whole
+// load latency lands in every step.  Naming the value here makes it settle the load before the
+// loop instead.
+template <class T>
+__device__ __forceinline__ void settle(T& v) {
+  asm volatile("" : "+v"(v));
 }
 
 // chunk c of row r is stored at chunk c ^ swz(r): a bijection over any 16 consecutive rows (row
@@ -180,6 +192,8 @@ __global__ void __launch_bounds__(NWAVES * 64, 2) attn_fwd_kernel(AttnArgs a) {
   bf16x8 qf[8];
 #pragma unroll
   for (int ks = 0; ks < 8; ++ks) qf[ks] = global_rows_frag(qb, rs, q_load, ks, lane);
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) settle(qf[ks]);
 
   f32x16 o[4];
 #pragma unroll
@@ -341,8 +355,15 @@ __global__ void __launch_bounds__(NWAVES * 64, 2) attn_dq_kernel(AttnArgs a) {
     dof[ks] = global_rows_frag(dob, rs, q_load, ks, lane);
   }
   const int64_t stat = ((int64_t)b * H + h) * L + q_load;
-  const float lse2 = a.lse_in[stat] * kLog2e, dls = a.delta_in[stat] * a.scale;
+  float lse2 = a.lse_in[stat] * kLog2e, dls = a.delta_in[stat] * a.scale;
   const float c2 = a.scale * kLog2e;
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) {
+    settle(qf[ks]);
+    settle(dof[ks]);
+  }
+  settle(lse2);
+  settle(dls);
 
   f32x16 dq[4];
 #pragma unroll
@@ -373,7 +394,10 @@ __global__ void __launch_bounds__(NWAVES * 64, 2) attn_dq_kernel(AttnArgs a) {
       for (int jj = 0; jj < 16; ++jj) {
         const float p = __builtin_amdgcn_exp2f(fmaf(s[jj], c2, -lse2));
         ds[jj] = p * fmaf(dp[jj], a.scale, -dls);  // p * (dp - delta) * scale
-        if (need_mask) {
+      }
+      if (need_mask) {  // one wave-uniform branch; whatever a hidden pair produced is discarded
+#pragma unroll
+        for (int jj = 0; jj < 16; ++jj) {
           const int kv = kv0 + kvb * 32 + acc_row(jj, hf);
           const bool vis = kv < L && (!a.causal || kv <= q_lane);
           ds[jj] = vis ? ds[jj] : 0.f;
@@ -428,6 +452,11 @@ __global__ void __launch_bounds__(NWAVES * 64, 1) attn_dkv_kernel(AttnArgs a) {
     kf[ks] = global_rows_frag(kb, rs, kv_load, ks, lane);
     vf[ks] = global_rows_frag(vb, rs, kv_load, ks, lane);
   }
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) {
+    settle(kf[ks]);
+    settle(vf[ks]);
+  }
   const float c2 = a.scale * kLog2e;
   f32x16 dk[4], dv[4];
 #pragma unroll
@@ -438,14 +467,25 @@ __global__ void __launch_bounds__(NWAVES * 64, 1) attn_dkv_kernel(AttnArgs a) {
 
   const int t_begin = a.causal ? kvblk0 / kTileRows : 0;  // earlier queries see none of these rows
   const int t_end = (L + kTileRows - 1) / kTileRows;
-  auto issue = [&](int t, char* st, float* stats) {
+  // The per-query statistics of a tile travel through registers of the first 64 threads: loaded
+  // with the tile (no wait), written to LDS after the wait that ends the tile's flight.
+  float st_lse = 0.f, st_delta = 0.f;
+  auto issue = [&](int t, char* st) {
     const int q0 = t * kTileRows;
     load_tile<NWAVES>(qb, (uint32_t)(rs * 2), q0, L, st, wave, lane);
     load_tile<NWAVES>(dob, (uint32_t)(rs * 2), q0, L, st + kTileBytes, wave, lane);
     if (threadIdx.x < kTileRows) {
       const int qi = min(q0 + (int)threadIdx.x, L - 1);
-      stats[threadIdx.x] = lse_row[qi] * kLog2e;
-      stats[kTileRows + threadIdx.x] = delta_row[qi] * a.scale;
+      st_lse = lse_row[qi];
+      st_delta = delta_row[qi];
+    }
+  };
+  // Called between the wait and the barrier that open a step: every wave is past its reads of
+  // the tile that used `stats` two steps ago (it passed the previous barrier after them).
+  auto commit_stats = [&](float* stats) {
+    if (threadIdx.x < kTileRows) {
+      stats[threadIdx.x] = st_lse * kLog2e;
+      stats[kTileRows + threadIdx.x] = st_delta * a.scale;
     }
   };
   auto process = [&](int t, const char* st, const float* stats) {
@@ -474,16 +514,17 @@ __global__ void __launch_bounds__(NWAVES * 64, 1) attn_dkv_kernel(AttnArgs a) {
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const int jj = g4 * 4 + e;
-          float pe = __builtin_amdgcn_exp2f(fmaf(s[jj], c2, -l4[e]));
-          float de = pe * fmaf(dp[jj], a.scale, -d4[e]);  // p * (dp - delta) * scale
-          if (need_mask) {
-            const int qi = q0 + r0 + e;
-            const bool vis = qi < L && kv_lane < L && (!a.causal || kv_lane <= qi);
-            pe = vis ? pe : 0.f;
-            de = vis ? de : 0.f;
-          }
-          p[jj] = pe;
-          ds[jj] = de;
+          p[jj] = __builtin_amdgcn_exp2f(fmaf(s[jj], c2, -l4[e]));
+          ds[jj] = p[jj] * fmaf(dp[jj], a.scale, -d4[e]);  // p * (dp - delta) * scale
+        }
+      }
+      if (need_mask) {  // one wave-uniform branch; whatever a hidden pair produced is discarded
+#pragma unroll
+        for (int jj = 0; jj < 16; ++jj) {
+          const int qi = q0 + qblk * 32 + acc_row(jj, hf);
+          const bool vis = qi < L && kv_lane < L && (!a.causal || kv_lane <= qi);
+          p[jj] = vis ? p[jj] : 0.f;
+          ds[jj] = vis ? ds[jj] : 0.f;
         }
       }
       pf[qblk * 2 + 0] = pack8(p);
@@ -501,14 +542,18 @@ __global__ void __launch_bounds__(NWAVES * 64, 1) attn_dkv_kernel(AttnArgs a) {
                                                           dk[blk], 0, 0, 0);
       }
   };
-  issue(t_begin, stage0, stats0);
+  issue(t_begin, stage0);
   for (int t = t_begin; t < t_end; t += 2) {
-    wait_loads_then_barrier();
-    if (t + 1 < t_end) issue(t + 1, stage1, stats1);
+    wait_loads();
+    commit_stats(stats0);
+    __syncthreads();
+    if (t + 1 < t_end) issue(t + 1, stage1);
     process(t, stage0, stats0);
     if (t + 1 >= t_end) break;
-    wait_loads_then_barrier();
-    if (t + 2 < t_end) issue(t + 2, stage0, stats0);
+    wait_loads();
+    commit_stats(stats1);
+    __syncthreads();
+    if (t + 2 < t_end) issue(t + 2, stage0);
     process(t + 1, stage1, stats1);
   }
   store_rows_bf16(a.out0 + head0, rs, kv_lane, L, dk, 1.f, lane);

@@ -22,6 +22,8 @@
 //     each XCD (own L2) work on a compact patch of C.
 #include "gemm_bf16.h"
 
+#include <type_traits>
+
 #include "timing.h"
 
 #include <cstdio>
@@ -48,11 +50,8 @@ struct TileCfg {
   static constexpr int kATile = BM * BK * 2, kBTile = BN * BK * 2, kStage = kATile + kBTile;  // bytes
   static constexpr int kGroupM = GROUP_M_;  // tile rows per L2 patch
   static constexpr int kStages = STAGES_;   // k-tiles resident in LDS (one computing, the rest in flight)
-  static constexpr int kFragAhead = TM * TN >= 8 ? 1 : 2;  // k-steps of fragments fetched ahead
-  // Where in a k-tile the loads of the next one are issued: after the first step's MFMAs (keeps
-  // the matrix cores fed across the tile boundary; pays off when a step has many MFMAs) or
-  // right after the barrier.
-  static constexpr bool kLateIssue = false;  // measured: no consistent gain at either tile shape
+  // k-steps (of 16) of fragments fetched ahead; kFragAhead + 1 must divide the steps per k-tile
+  static constexpr int kFragAhead = TM * TN >= 8 ? 1 : 3;
   static constexpr int kWavesPerSimd = 2;  // register budget: two wavefronts per SIMD
 };
 using LargeTile = TileCfg<256, 256, 2, 4, 4, 2>;      // 128 KiB LDS, one workgroup per CU
@@ -266,46 +265,24 @@ __global__ void __launch_bounds__(Cfg::kThreads, Cfg::kWavesPerSimd) gemm_bf16_k
     next_b += b_tile_bytes;
     next_left -= BK;
   };
-  // One k-tile = 4 steps of 16.  LDS->register latency is several hundred cycles, more than the
-  // MFMAs of one step take, so fragments are fetched kAhead steps ahead into a rotating set of
-  // kAhead+1 register buffers: one LDS read is slotted in front of each of the first TM+TN MFMAs
-  // of a step.
+  // One k-tile = BK/16 steps of 16.  LDS->register latency is several hundred cycles, more than
+  // the MFMAs of one step take, so fragments are fetched kAhead steps ahead into a rotating set
+  // of kAhead+1 register buffers (one LDS read slotted in front of each of the first TM+TN MFMAs
+  // of a step) - and the fetch-ahead runs across k-tile boundaries: the barrier that publishes
+  // tile kt+1 stands kAhead steps before the end of tile kt, right where this wave has fetched
+  // the last fragment of tile kt.  The MFMAs still to do on tile kt then cover both the latency
+  // of the first fragments of tile kt+1 and the issue of the loads of a further tile.
   constexpr int kAhead = Cfg::kFragAhead;
+  constexpr int kSteps = BK / 16;
+  static_assert(kSteps % (kAhead + 1) == 0, "fragment buffers must rotate back at a tile boundary");
+  static_assert(kAhead < kSteps, "fetch-ahead of at most one k-tile");
+  bf16x8 af[kAhead + 1][TM], bf[kAhead + 1][TN];
   auto fetch = [&](const char* st, int ks, bf16x8* a_dst, bf16x8* b_dst, int which) {
     // which: 0..TN-1 -> B fragment, TN..TN+TM-1 -> A fragment
     if (which < TN)
       b_dst[which] = read_fragment<B_K, BN>(st + Cfg::kATile, wave_n + which * 32, ks, lane);
     else
       a_dst[which - TN] = read_fragment<A_K, BM>(st, wave_m + (which - TN) * 32, ks, lane);
-  };
-  // `next_stage` (or nullptr): where to start loading the next k-tile; done after the first
-  // step's MFMAs are under way, so the matrix cores are not kept waiting for the load issue.
-  auto compute = [&](const char* st, char* next_stage) {
-    bf16x8 af[kAhead + 1][TM], bf[kAhead + 1][TN];
-    if (!Cfg::kLateIssue && next_stage) issue_next(next_stage);
-#pragma unroll
-    for (int p = 0; p < kAhead; ++p)
-#pragma unroll
-      for (int w = 0; w < TM + TN; ++w) fetch(st, p, af[p], bf[p], w);
-#pragma unroll
-    for (int ks = 0; ks < BK / 16; ++ks) {
-      const int cur = ks % (kAhead + 1), nxt = (ks + kAhead) % (kAhead + 1);
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-          const int slot = i * TN + j;  // MFMA number within the step
-          if (ks + kAhead < BK / 16 && slot < TM + TN) fetch(st, ks + kAhead, af[nxt], bf[nxt], slot);
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[cur][j], af[cur][i], acc[i][j], 0, 0, 0);
-          // keep this read-then-MFMA order: left alone, the scheduler sinks every read to just
-          // before its first use (fewer live registers) and the overlap is lost
-          __builtin_amdgcn_sched_barrier(0);
-        }
-      if (Cfg::kLateIssue && ks == 0 && next_stage) {
-        issue_next(next_stage);
-        __builtin_amdgcn_sched_barrier(0);
-      }
-    }
   };
   // Loads complete in issue order, so "tile kt has landed" = at most the loads of the newer tiles
   // are still outstanding.  A ragged tile may issue fewer than the usual number of loads per wave,
@@ -320,20 +297,73 @@ __global__ void __launch_bounds__(Cfg::kThreads, Cfg::kWavesPerSimd) gemm_bf16_k
       asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kLoadsPerTile) : "memory");
     else
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    // passing the barrier also means everyone finished computing on tile kt-1, whose stage the
-    // next issue overwrites
+    // Passing the barrier also means every wave has fetched its last fragment of the tile being
+    // computed on (the barrier waits for the wave's own LDS reads first), so that tile's stage
+    // may be overwritten by the next issue.
     __syncthreads();
   };
-
+  // MFMAs of tile kt (in stage `st`); HAS_NEXT: tile kt+1 exists (in `st_next`), and `fill`
+  // (or nullptr) is the stage - the one tile kt occupies when NS == 2 - a further tile goes to.
+  auto compute = [&](auto has_next, int kt, const char* st, const char* st_next, char* fill) {
+    constexpr bool HAS_NEXT = decltype(has_next)::value;
 #pragma unroll
-  for (int p = 0; p < NS - 1; ++p)
+    for (int ks = 0; ks < kSteps; ++ks) {
+      const int cur = ks % (kAhead + 1), nxt = (ks + kAhead) % (kAhead + 1);
+      const bool crosses = ks + kAhead >= kSteps;  // the fetch of this step reads the next tile
+      if (HAS_NEXT && ks + kAhead == kSteps) {
+        wait_for_tile(kt + 1);
+        if (fill) issue_next(fill);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+          const int slot = i * TN + j;  // MFMA number within the step
+          if (slot < TM + TN) {
+            if (!crosses)
+              fetch(st, ks + kAhead, af[nxt], bf[nxt], slot);
+            else if (HAS_NEXT)
+              fetch(st_next, ks + kAhead - kSteps, af[nxt], bf[nxt], slot);
+          }
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[cur][j], af[cur][i], acc[i][j], 0, 0, 0);
+          // keep this read-then-MFMA order: left alone, the scheduler sinks every read to just
+          // before its first use (fewer live registers) and the overlap is lost
+          __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+  };
+
+  // Prologue: fill the ring (NS == 2: both stages are free, so two tiles go out at once), wait
+  // for tile 0 and fetch its first kAhead steps.
+#pragma unroll
+  for (int p = 0; p < NS; ++p)
     if (p < total_tiles) issue_next(ring + p * Cfg::kStage);
-  int stage = 0, fill = NS - 1;  // stage of tile kt; stage that tile kt+NS-1 goes to
-  for (int kt = 0; kt < total_tiles; ++kt) {
-    wait_for_tile(kt);
-    compute(ring + stage * Cfg::kStage, kt + NS - 1 < total_tiles ? ring + fill * Cfg::kStage : nullptr);
-    stage = stage + 1 == NS ? 0 : stage + 1;
-    fill = fill + 1 == NS ? 0 : fill + 1;
+  if (total_tiles > 0) {
+    {
+      // tiles 1 .. NS-1 were issued after tile 0
+      const int newer = min(NS - 1, total_tiles - 1);
+      const int allowed = newer > 0 ? __builtin_popcount(full_hist & ((1u << newer) - 1u)) : 0;
+      if (allowed >= NS - 1 && NS == 2)
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kLoadsPerTile) : "memory");
+      else
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      __syncthreads();
+    }
+#pragma unroll
+    for (int p = 0; p < kAhead; ++p)
+#pragma unroll
+      for (int w = 0; w < TM + TN; ++w) fetch(ring, p, af[p], bf[p], w);
+    // Tile kt sits in stage kt % NS.  At the boundary inside compute(kt) the stage of tile kt is
+    // released and refilled with tile kt+NS.
+    int stage = 0;
+    for (int kt = 0; kt + 1 < total_tiles; ++kt) {
+      const int nstage = stage + 1 == NS ? 0 : stage + 1;
+      compute(std::true_type{}, kt, ring + stage * Cfg::kStage, ring + nstage * Cfg::kStage,
+              kt + NS < total_tiles ? ring + stage * Cfg::kStage : nullptr);
+      stage = nstage;
+    }
+    compute(std::false_type{}, total_tiles - 1, ring + stage * Cfg::kStage, nullptr, nullptr);
   }
 
   if (g.debug_clocks && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) {

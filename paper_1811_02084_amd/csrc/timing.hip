@@ -3,6 +3,8 @@
 // totals.  Used by the benchmark to time the dominant kernel inside the timed region.
 #include "timing.h"
 
+#include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <mutex>
 #include <vector>
@@ -70,6 +72,10 @@ int mtf_timing_collect(mtf_kernel_time* out, int32_t max_kinds, int32_t* n_kinds
   std::lock_guard<std::mutex> lock(g_mu);
   int n = 0;
   int rc = MTF_OK;
+  // tuning aid: MTF_TIMING_TRACE=1 lists every launch in issue order on stderr
+  const char* trace_env = std::getenv("MTF_TIMING_TRACE");
+  const bool trace = trace_env && trace_env[0] == '1';
+  int seq = 0;
   for (Record& r : g_records) {
     float ms = 0.f;
     hipError_t e = hipEventSynchronize(r.stop);
@@ -78,6 +84,9 @@ int mtf_timing_collect(mtf_kernel_time* out, int32_t max_kinds, int32_t* n_kinds
     g_free_events.push_back(r.start);
     g_free_events.push_back(r.stop);
     if (e != hipSuccess) continue;
+    if (trace)
+      std::fprintf(stderr, "[mtf timing] %4d %8.2f us %8.1f TFLOP/s %8.1f GB/s  %s\n", seq++, ms * 1e3,
+                   r.flops / ms * 1e-9, r.bytes / ms * 1e-6, r.kind);
     int k = 0;
     while (k < n && std::strcmp(out[k].kernel, r.kind) != 0) ++k;
     if (k == n) {
