@@ -180,9 +180,9 @@ __global__ void __launch_bounds__(NWAVES * 64, 2) attn_fwd_kernel(AttnArgs a) {
   const int lane = threadIdx.x & 63, hf = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int L = a.length, H = a.heads;
-  const int b = blockIdx.z, h = blockIdx.y;
+  const int b = blockIdx.y, h = blockIdx.x;
   // causal: later query blocks see more memory positions; start those first
-  const int q0 = (a.causal ? gridDim.x - 1 - blockIdx.x : blockIdx.x) * (NWAVES * 32);
+  const int q0 = (a.causal ? gridDim.z - 1 - blockIdx.z : blockIdx.z) * (NWAVES * 32);
   const int64_t rs = (int64_t)H * kHeadDim;
   const int64_t head0 = ((int64_t)b * L) * rs + (int64_t)h * kHeadDim;
   const bf16_t *qb = a.q + head0, *kb = a.k + head0, *vb = a.v + head0;
@@ -339,9 +339,9 @@ __global__ void __launch_bounds__(NWAVES * 64, 2) attn_dq_kernel(AttnArgs a) {
   const int lane = threadIdx.x & 63, hf = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int L = a.length, H = a.heads;
-  const int b = blockIdx.z, h = blockIdx.y;
+  const int b = blockIdx.y, h = blockIdx.x;
   // causal: later query blocks see more memory positions; start those first
-  const int q0 = (a.causal ? gridDim.x - 1 - blockIdx.x : blockIdx.x) * (NWAVES * 32);
+  const int q0 = (a.causal ? gridDim.z - 1 - blockIdx.z : blockIdx.z) * (NWAVES * 32);
   const int64_t rs = (int64_t)H * kHeadDim;
   const int64_t head0 = ((int64_t)b * L) * rs + (int64_t)h * kHeadDim;
   const bf16_t *qb = a.q + head0, *kb = a.k + head0, *vb = a.v + head0, *dob = a.dctx + head0;
@@ -436,8 +436,8 @@ __global__ void __launch_bounds__(NWAVES * 64, 1) attn_dkv_kernel(AttnArgs a) {
   const int lane = threadIdx.x & 63, hf = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int L = a.length, H = a.heads;
-  const int b = blockIdx.z, h = blockIdx.y;
-  const int kvblk0 = blockIdx.x * (NWAVES * 32);
+  const int b = blockIdx.y, h = blockIdx.x;
+  const int kvblk0 = blockIdx.z * (NWAVES * 32);  // causal: early memory rows are seen by more queries
   const int64_t rs = (int64_t)H * kHeadDim;
   const int64_t head0 = ((int64_t)b * L) * rs + (int64_t)h * kHeadDim;
   const bf16_t *qb = a.q + head0, *kb = a.k + head0, *vb = a.v + head0, *dob = a.dctx + head0;
@@ -488,35 +488,63 @@ __global__ void __launch_bounds__(NWAVES * 64, 1) attn_dkv_kernel(AttnArgs a) {
       stats[kTileRows + threadIdx.x] = st_delta * a.scale;
     }
   };
+  // One wave per SIMD here, so nothing but this wave's own instruction order hides the LDS
+  // latency: every operand fragment is fetched kDepth MFMA pairs ahead of its use, through rings
+  // of kDepth+1 register buffers, and a scheduling barrier after each pair keeps that order (left
+  // alone, the scheduler sinks each read to just before its MFMA and every pair waits out a full
+  // LDS round trip).
+  constexpr int kDepth = 3;
   auto process = [&](int t, const char* st, const float* stats) {
     const int q0 = t * kTileRows;
     const char *qt_ = st, *dot_ = st + kTileBytes;
     const float *lset_ = stats, *delt_ = stats + kTileRows;
     if (a.causal && q0 + kTileRows - 1 < kvblk0 + wave * 32) return;  // all queries precede this wave's rows
     bf16x8 pf[4], dsf[4];
+    // first products: item n = qblk*8 + ks -> (Q rows, dO rows) fragments of k-step ks
+    bf16x8 fq[kDepth + 1], fo[kDepth + 1];
+    auto fetch_rows = [&](int n) {
+      fq[n & kDepth] = rows_frag(qt_, (n >> 3) * 32, n & 7, lane);
+      fo[n & kDepth] = rows_frag(dot_, (n >> 3) * 32, n & 7, lane);
+    };
+    // second products: item n = blk*4 + t -> (dO^T, Q^T) fragments of 32 columns x 16 queries
+    bf16x8 co[kDepth + 1], cq[kDepth + 1];
+    auto fetch_cols = [&](int n) {
+      co[n & kDepth] = cols_frag(dot_, (n >> 2) * 32, (n & 3) * 16, lane);
+      cq[n & kDepth] = cols_frag(qt_, (n >> 2) * 32, (n & 3) * 16, lane);
+    };
+    static_assert((kDepth & (kDepth + 1)) == 0, "ring index by mask");
+#pragma unroll
+    for (int n = 0; n < kDepth; ++n) fetch_rows(n);
 #pragma unroll
     for (int qblk = 0; qblk < 2; ++qblk) {
       f32x16 s = zero16(), dp = zero16();
+      // the statistics of this block's queries: read now, needed after the MFMAs
+      f32x4 l4[4], d4[4];  // lse * log2(e), delta * scale of 4 consecutive query rows per group
+#pragma unroll
+      for (int g4 = 0; g4 < 4; ++g4) {
+        const int r0 = qblk * 32 + g4 * 8 + hf * 4;
+        l4[g4] = *LDS_PTR(const f32x4, reinterpret_cast<const char*>(lset_) + r0 * 4);
+        d4[g4] = *LDS_PTR(const f32x4, reinterpret_cast<const char*>(delt_) + r0 * 4);
+      }
 #pragma unroll
       for (int ks = 0; ks < 8; ++ks) {
-        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rows_frag(qt_, qblk * 32, ks, lane), kf[ks], s, 0, 0, 0);
-        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rows_frag(dot_, qblk * 32, ks, lane), vf[ks], dp, 0, 0, 0);
+        const int n = qblk * 8 + ks;
+        if (n + kDepth < 16)
+          fetch_rows(n + kDepth);
+        else
+          fetch_cols(n + kDepth - 16);  // the last steps already bring in the second products' operands
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fq[n & kDepth], kf[ks], s, 0, 0, 0);
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fo[n & kDepth], vf[ks], dp, 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
       }
       float p[16], ds[16];
       // a hidden (query, memory) pair can only occur on ragged or diagonal tiles (wave-uniform)
       const bool need_mask = q0 + kTileRows > L || kvblk0 + wave * 32 + 32 > L ||
                              (a.causal && kvblk0 + wave * 32 + 31 > q0);
 #pragma unroll
-      for (int g4 = 0; g4 < 4; ++g4) {
-        const int r0 = qblk * 32 + g4 * 8 + hf * 4;  // 4 consecutive query rows of this group
-        const f32x4 l4 = *LDS_PTR(const f32x4, reinterpret_cast<const char*>(lset_) + r0 * 4);
-        const f32x4 d4 = *LDS_PTR(const f32x4, reinterpret_cast<const char*>(delt_) + r0 * 4);  // delta * scale
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const int jj = g4 * 4 + e;
-          p[jj] = __builtin_amdgcn_exp2f(fmaf(s[jj], c2, -l4[e]));
-          ds[jj] = p[jj] * fmaf(dp[jj], a.scale, -d4[e]);  // p * (dp - delta) * scale
-        }
+      for (int jj = 0; jj < 16; ++jj) {
+        p[jj] = __builtin_amdgcn_exp2f(fmaf(s[jj], c2, -l4[jj >> 2][jj & 3]));
+        ds[jj] = p[jj] * fmaf(dp[jj], a.scale, -d4[jj >> 2][jj & 3]);  // p * (dp - delta) * scale
       }
       if (need_mask) {  // one wave-uniform branch; whatever a hidden pair produced is discarded
 #pragma unroll
@@ -531,16 +559,16 @@ __global__ void __launch_bounds__(NWAVES * 64, 1) attn_dkv_kernel(AttnArgs a) {
       pf[qblk * 2 + 1] = pack8(p + 8);
       dsf[qblk * 2 + 0] = pack8(ds);
       dsf[qblk * 2 + 1] = pack8(ds + 8);
+      __builtin_amdgcn_sched_barrier(0);
     }
 #pragma unroll
-    for (int blk = 0; blk < 4; ++blk)
-#pragma unroll
-      for (int t = 0; t < 4; ++t) {
-        dv[blk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cols_frag(dot_, blk * 32, t * 16, lane), pf[t],
-                                                          dv[blk], 0, 0, 0);
-        dk[blk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cols_frag(qt_, blk * 32, t * 16, lane), dsf[t],
-                                                          dk[blk], 0, 0, 0);
-      }
+    for (int n = 0; n < 16; ++n) {
+      const int blk = n >> 2, tq = n & 3;
+      if (n + kDepth < 16) fetch_cols(n + kDepth);
+      dv[blk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(co[n & kDepth], pf[tq], dv[blk], 0, 0, 0);
+      dk[blk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cq[n & kDepth], dsf[tq], dk[blk], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    }
   };
   issue(t_begin, stage0);
   for (int t = t_begin; t < t_end; t += 2) {
@@ -563,7 +591,9 @@ __global__ void __launch_bounds__(NWAVES * 64, 1) attn_dkv_kernel(AttnArgs a) {
 int check_shape(const AttnShape& s) {
   if (s.batch <= 0 || s.length <= 0 || s.heads <= 0)
     return fail(MTF_ERR_SIZE_MISMATCH, "attention shape %d x %d x %d", s.batch, s.length, s.heads);
-  if (s.batch > 65535 || s.heads > 65535) return fail(MTF_ERR_UNSUPPORTED, "batch / heads > 65535");
+  // grid = (heads, batch, row blocks of >= 64 rows): heads vary fastest so that every XCD
+  // (workgroups go to XCDs round-robin) gets row blocks of every weight
+  if (s.batch > 65535 || s.length > 65535 * 64) return fail(MTF_ERR_UNSUPPORTED, "batch > 65535 or length > 65535*64");
   if ((int64_t)s.length * s.heads * kRowBytes >= (int64_t)1 << 32)
     return fail(MTF_ERR_UNSUPPORTED, "length * heads too large for 32-bit tile offsets");
   return MTF_OK;
@@ -599,7 +629,7 @@ int attn_fwd_launch(const AttnShape& s, const bf16_t* q, const bf16_t* k, const 
   const double flops = 2.0 * 2.0 * s.batch * s.heads * pairs * kHeadDim;
   const double bytes = 4.0 * s.batch * s.length * s.heads * kRowBytes;
   const int nw = waves_per_group(s, 8);
-  dim3 grid((unsigned)ceil_div(s.length, nw * 32), (unsigned)s.heads, (unsigned)s.batch);
+  dim3 grid((unsigned)s.heads, (unsigned)s.batch, (unsigned)ceil_div(s.length, nw * 32));
   if (nw == 8) {
     LaunchTimer timer("attn_fwd_kernel<8>", flops, bytes, stream);
     attn_fwd_kernel<8><<<grid, 512, 0, stream>>>(a);
@@ -630,7 +660,7 @@ int attn_bwd_launch(const AttnShape& s, const bf16_t* q, const bf16_t* k, const 
   a.q = q; a.k = k; a.v = v; a.dctx = dctx; a.lse_in = lse; a.delta_in = delta;
   {  // dq = einsum(ds, k): 1 of the 4 backward contractions (the recomputed logits and dp are overhead here)
     const int nw = waves_per_group(s, 8);
-    dim3 grid((unsigned)ceil_div(s.length, nw * 32), (unsigned)s.heads, (unsigned)s.batch);
+    dim3 grid((unsigned)s.heads, (unsigned)s.batch, (unsigned)ceil_div(s.length, nw * 32));
     a.out0 = dq;
     LaunchTimer timer(nw == 8 ? "attn_dq_kernel<8>" : nw == 4 ? "attn_dq_kernel<4>" : "attn_dq_kernel<2>", unit,
                       5.0 * act, stream);
@@ -643,7 +673,7 @@ int attn_bwd_launch(const AttnShape& s, const bf16_t* q, const bf16_t* k, const 
   }
   if (int rc = launch_status("attn_dq_kernel")) return rc;
   const int nw = waves_per_group(s, 4);
-  dim3 grid((unsigned)ceil_div(s.length, nw * 32), (unsigned)s.heads, (unsigned)s.batch);
+  dim3 grid((unsigned)s.heads, (unsigned)s.batch, (unsigned)ceil_div(s.length, nw * 32));
   a.out0 = dk;
   a.out1 = dv;
   {  // dp, dv, dk: 3 of the 4 backward contractions
