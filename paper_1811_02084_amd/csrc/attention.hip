@@ -170,6 +170,34 @@ __device__ __forceinline__ void store_rows_bf16(bf16_t* base, int64_t row_stride
     }
 }
 
+// Query rows of a workgroup.  With 8 waves the workgroup takes two blocks of 128 query rows, one
+// from each end of the sequence (waves 0-3 the later block, waves 4-7 the earlier one): under the
+// causal mask a late block sees many memory tiles and an early one few, and a wave of each kind
+// lands on every SIMD (wave w runs on SIMD w % 4), so all SIMDs of all CUs get the same work.
+// Smaller workgroups take NWAVES*32 consecutive rows, later blocks first.
+struct QueryRows {
+  int wave_row0;  // first query row of this wave
+  int last_row;   // last query row of the workgroup (bounds the memory tiles a causal pass needs)
+  bool active;    // false: this wave has no rows (odd number of blocks, middle block)
+};
+template <int NWAVES>
+__device__ __forceinline__ QueryRows query_rows(int length, bool causal, int wave) {
+  QueryRows r;
+  if (NWAVES == 8) {
+    const int nblk = (length + 127) / 128;
+    const int late = nblk - 1 - (int)blockIdx.z, early = (int)blockIdx.z;
+    r.wave_row0 = (wave < 4 ? late : early) * 128 + (wave & 3) * 32;
+    r.last_row = late * 128 + 127;
+    r.active = wave < 4 || early != late;
+  } else {
+    const int q0 = (causal ? gridDim.z - 1 - blockIdx.z : blockIdx.z) * (NWAVES * 32);
+    r.wave_row0 = q0 + wave * 32;
+    r.last_row = q0 + NWAVES * 32 - 1;
+    r.active = true;
+  }
+  return r;
+}
+
 // ------------------------------------------------------------------------------------ forward
 // One workgroup: NWAVES*32 query rows of one (batch, head); each wave owns 32 of them.
 template <int NWAVES>
@@ -181,28 +209,43 @@ __global__ void __launch_bounds__(NWAVES * 64, 2) attn_fwd_kernel(AttnArgs a) {
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int L = a.length, H = a.heads;
   const int b = blockIdx.y, h = blockIdx.x;
-  // causal: later query blocks see more memory positions; start those first
-  const int q0 = (a.causal ? gridDim.z - 1 - blockIdx.z : blockIdx.z) * (NWAVES * 32);
+  const QueryRows qr = query_rows<NWAVES>(L, a.causal, wave);
+  const int q0w = qr.wave_row0;
   const int64_t rs = (int64_t)H * kHeadDim;
   const int64_t head0 = ((int64_t)b * L) * rs + (int64_t)h * kHeadDim;
   const bf16_t *qb = a.q + head0, *kb = a.k + head0, *vb = a.v + head0;
 
-  const int q_lane = q0 + wave * 32 + (lane & 31);  // this lane's query row
+  const int q_lane = q0w + (lane & 31);  // this lane's query row
   const int q_load = min(q_lane, L - 1);
   bf16x8 qf[8];
 #pragma unroll
   for (int ks = 0; ks < 8; ++ks) qf[ks] = global_rows_frag(qb, rs, q_load, ks, lane);
 #pragma unroll
   for (int ks = 0; ks < 8; ++ks) settle(qf[ks]);
+  // The running maximum works on s * c with c >= 0.  A negative scale is moved into q (sign
+  // bits flipped: logits come out negated); a zero scale becomes a tiny positive one (logits
+  // of order 1e-30 instead of 0), which keeps -inf * c = -inf for hidden positions.
+  if (a.scale < 0.f) {
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+      union {
+        bf16x8 v;
+        uint32_t w[4];
+      } u;
+      u.v = qf[ks];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) u.w[i] ^= 0x80008000u;
+      qf[ks] = u.v;
+    }
+  }
 
   f32x16 o[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) o[i] = zero16();
   float m2 = -INFINITY, lsum = 0.f;  // running max (log2 units) and row sum
-  const float c2 = fabsf(a.scale) * kLog2e;
-  const bool negate = a.scale < 0.f;  // max(s * c) needs c >= 0: use (-s) * |c| instead
+  const float c2 = fmaxf(fabsf(a.scale) * kLog2e, 1e-30f);
 
-  const int kv_end = a.causal ? min(L, q0 + NWAVES * 32) : L;
+  const int kv_end = a.causal ? min(L, qr.last_row + 1) : L;
   const int n_tiles = (kv_end + kTileRows - 1) / kTileRows;
   auto issue = [&](int t, char* st) {
     load_tile<NWAVES>(kb, (uint32_t)(rs * 2), t * kTileRows, L, st, wave, lane);
@@ -211,7 +254,7 @@ __global__ void __launch_bounds__(NWAVES * 64, 2) attn_fwd_kernel(AttnArgs a) {
   auto process = [&](int t, const char* st) {
     const int kv0 = t * kTileRows;
     const char *kt_ = st, *vt_ = st + kTileBytes;
-    if (a.causal && kv0 > q0 + wave * 32 + 31) return;  // nothing visible for this wave
+    if (!qr.active || (a.causal && kv0 > q0w + 31)) return;  // nothing visible for this wave
     // logits^T: rows = memory positions of the tile, column = this lane's query
     f32x16 s[2];
 #pragma unroll
@@ -222,18 +265,12 @@ __global__ void __launch_bounds__(NWAVES * 64, 2) attn_fwd_kernel(AttnArgs a) {
         s[kvb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rows_frag(kt_, kvb * 32, ks, lane), qf[ks],
                                                          s[kvb], 0, 0, 0);
     }
-    if (negate) {
-#pragma unroll
-      for (int kvb = 0; kvb < 2; ++kvb)
-#pragma unroll
-        for (int jj = 0; jj < 16; ++jj) s[kvb][jj] = -s[kvb][jj];
-    }
     // Softmax bookkeeping, kept cheap on the vector ALU (it competes with the matrix cores):
     //  * masking only on tiles that can contain a hidden position for this wave (wave-uniform);
     //  * the scale is folded into one fma per logit: p = exp2(s * c2 - m);
     //  * the running maximum m2 is only raised (and O, lsum rescaled) when some row's maximum
     //    exceeds it by more than kSlack: until then p <= 2^kSlack, harmless in fp32 / bf16.
-    const bool need_mask = kv0 + kTileRows > L || (a.causal && kv0 + kTileRows - 1 > q0 + wave * 32);
+    const bool need_mask = kv0 + kTileRows > L || (a.causal && kv0 + kTileRows - 1 > q0w);
     if (need_mask) {
 #pragma unroll
       for (int kvb = 0; kvb < 2; ++kvb)
@@ -250,7 +287,7 @@ __global__ void __launch_bounds__(NWAVES * 64, 2) attn_fwd_kernel(AttnArgs a) {
 #pragma unroll
       for (int jj = 0; jj < 16; ++jj) mx = fmaxf(mx, s[kvb][jj]);
     mx = fmaxf(mx, __shfl_xor(mx, 32));  // the other half-wave holds the rest of this query's row
-    mx = mx == -INFINITY ? mx : mx * c2;  // c2 >= 0 (logits were negated for a negative scale)
+    mx *= c2;  // c2 > 0, so a fully hidden row stays at -inf
     constexpr float kSlack = 8.f;
     if (__any(mx > m2 + kSlack)) {  // first tile: m2 = -inf, always taken; position 0 is visible
       const float m_new = fmaxf(m2, mx);
@@ -269,10 +306,8 @@ __global__ void __launch_bounds__(NWAVES * 64, 2) attn_fwd_kernel(AttnArgs a) {
       float p[16];
 #pragma unroll
       for (int jj = 0; jj < 16; ++jj) {
-        float pe = __builtin_amdgcn_exp2f(fmaf(s[kvb][jj], c2, -m2));
-        if (need_mask) pe = s[kvb][jj] == -INFINITY ? 0.f : pe;  // also covers c2 == 0 (0 * inf)
-        p[jj] = pe;
-        psum += pe;
+        p[jj] = __builtin_amdgcn_exp2f(fmaf(s[kvb][jj], c2, -m2));  // hidden: exp2(-inf) = 0
+        psum += p[jj];
       }
       pf[kvb * 2 + 0] = pack8(p);
       pf[kvb * 2 + 1] = pack8(p + 8);
@@ -289,15 +324,14 @@ __global__ void __launch_bounds__(NWAVES * 64, 2) attn_fwd_kernel(AttnArgs a) {
   // Two stages: the tile after the one being processed is in flight.  Passing the barrier means
   // everyone has the current tile and is done with the stage the next issue() overwrites.
   issue(0, stage0);
-  for (int t = 0; t < n_tiles; t += 2) {
+  for (int t = 0; t < n_tiles; ++t) {
+    char* cur = (t & 1) ? stage1 : stage0;
+    char* nxt = (t & 1) ? stage0 : stage1;
     wait_loads_then_barrier();
-    if (t + 1 < n_tiles) issue(t + 1, stage1);
-    process(t, stage0);
-    if (t + 1 >= n_tiles) break;
-    wait_loads_then_barrier();
-    if (t + 2 < n_tiles) issue(t + 2, stage0);
-    process(t + 1, stage1);
+    if (t + 1 < n_tiles) issue(t + 1, nxt);
+    process(t, cur);
   }
+  if (!qr.active) return;
   store_rows_bf16(a.out0 + head0, rs, q_lane, L, o, 1.f / lsum, lane);
   if (q_lane < L && hf == 0)
     a.lse_out[((int64_t)b * H + h) * L + q_lane] = (m2 + __log2f(lsum)) * kLn2;
@@ -340,13 +374,13 @@ __global__ void __launch_bounds__(NWAVES * 64, 2) attn_dq_kernel(AttnArgs a) {
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int L = a.length, H = a.heads;
   const int b = blockIdx.y, h = blockIdx.x;
-  // causal: later query blocks see more memory positions; start those first
-  const int q0 = (a.causal ? gridDim.z - 1 - blockIdx.z : blockIdx.z) * (NWAVES * 32);
+  const QueryRows qr = query_rows<NWAVES>(L, a.causal, wave);
+  const int q0w = qr.wave_row0;
   const int64_t rs = (int64_t)H * kHeadDim;
   const int64_t head0 = ((int64_t)b * L) * rs + (int64_t)h * kHeadDim;
   const bf16_t *qb = a.q + head0, *kb = a.k + head0, *vb = a.v + head0, *dob = a.dctx + head0;
 
-  const int q_lane = q0 + wave * 32 + (lane & 31);
+  const int q_lane = q0w + (lane & 31);
   const int q_load = min(q_lane, L - 1);
   bf16x8 qf[8], dof[8];
 #pragma unroll
@@ -369,7 +403,7 @@ __global__ void __launch_bounds__(NWAVES * 64, 2) attn_dq_kernel(AttnArgs a) {
 #pragma unroll
   for (int i = 0; i < 4; ++i) dq[i] = zero16();
 
-  const int kv_end = a.causal ? min(L, q0 + NWAVES * 32) : L;
+  const int kv_end = a.causal ? min(L, qr.last_row + 1) : L;
   const int n_tiles = (kv_end + kTileRows - 1) / kTileRows;
   auto issue = [&](int t, char* st) {
     load_tile<NWAVES>(kb, (uint32_t)(rs * 2), t * kTileRows, L, st, wave, lane);
@@ -378,7 +412,7 @@ __global__ void __launch_bounds__(NWAVES * 64, 2) attn_dq_kernel(AttnArgs a) {
   auto process = [&](int t, const char* st) {
     const int kv0 = t * kTileRows;
     const char *kt_ = st, *vt_ = st + kTileBytes;
-    if (a.causal && kv0 > q0 + wave * 32 + 31) return;
+    if (!qr.active || (a.causal && kv0 > q0w + 31)) return;
     bf16x8 dsf[4];
 #pragma unroll
     for (int kvb = 0; kvb < 2; ++kvb) {
@@ -389,7 +423,7 @@ __global__ void __launch_bounds__(NWAVES * 64, 2) attn_dq_kernel(AttnArgs a) {
         dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rows_frag(vt_, kvb * 32, ks, lane), dof[ks], dp, 0, 0, 0);
       }
       float ds[16];
-      const bool need_mask = kv0 + kTileRows > L || (a.causal && kv0 + kTileRows - 1 > q0 + wave * 32);
+      const bool need_mask = kv0 + kTileRows > L || (a.causal && kv0 + kTileRows - 1 > q0w);
 #pragma unroll
       for (int jj = 0; jj < 16; ++jj) {
         const float p = __builtin_amdgcn_exp2f(fmaf(s[jj], c2, -lse2));
@@ -414,15 +448,14 @@ __global__ void __launch_bounds__(NWAVES * 64, 2) attn_dq_kernel(AttnArgs a) {
                                                           dq[blk], 0, 0, 0);
   };
   issue(0, stage0);
-  for (int t = 0; t < n_tiles; t += 2) {
+  for (int t = 0; t < n_tiles; ++t) {
+    char* cur = (t & 1) ? stage1 : stage0;
+    char* nxt = (t & 1) ? stage0 : stage1;
     wait_loads_then_barrier();
-    if (t + 1 < n_tiles) issue(t + 1, stage1);
-    process(t, stage0);
-    if (t + 1 >= n_tiles) break;
-    wait_loads_then_barrier();
-    if (t + 2 < n_tiles) issue(t + 2, stage0);
-    process(t + 1, stage1);
+    if (t + 1 < n_tiles) issue(t + 1, nxt);
+    process(t, cur);
   }
+  if (!qr.active) return;
   store_rows_bf16(a.out0 + head0, rs, q_lane, L, dq, 1.f, lane);
 }
 
