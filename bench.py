@@ -6,6 +6,10 @@ backward of a full Transformer-layer shard (attention + feed-forward sublayers w
 residual adds), every contraction in the library's HIP kernels.  Prints ONE JSON line.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload layer|ffn|mha]
+
+`--workload copy` is not a benchmark of the path: it launches the library's plain copy kernel
+(fp32 -> fp32 cast) on a buffer of known size, which is what the HBM counters of a profiler run
+are scaled by (see roofline.traffic).
 """
 import argparse
 import json
@@ -36,7 +40,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="layer", choices=["layer", "ffn", "mha"])
+    ap.add_argument("--workload", default="layer", choices=["layer", "ffn", "mha", "copy"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -53,6 +57,9 @@ def main():
         return 2
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+
+    if args.workload == "copy":
+        return copy_calibration(args, torch, mtf, dev)
 
     # ---------------------------------------------------------------- workload
     if args.workload == "layer":
@@ -121,7 +128,8 @@ def main():
     avg_ms = dom["total_ms"] / dom["launches"]
     achieved = dom["flops"] / dom["launches"] / (avg_ms * 1e-3) / 1e12
     roofline = dict(bound="mfma", achieved=round(achieved, 1), peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
-                    frac=round(achieved / PEAK_BF16_TFLOPS, 4), traffic=None,
+                    frac=round(achieved / PEAK_BF16_TFLOPS, 4),
+                    traffic=measured_traffic(args.workload, dom["kernel"]),
                     kernel=dom["kernel"], launches_per_step=dom["launches"] // args.steps,
                     avg_launch_us=round(avg_ms * 1e3, 2))
     all_ms = sum(r["total_ms"] for r in kinds)
@@ -154,6 +162,46 @@ def main():
     }
     print(json.dumps(out))
     return 0
+
+
+COPY_ELEMS = 1 << 28            # fp32 elements: 1 GiB read + 1 GiB written per launch
+
+
+def copy_calibration(args, torch, mtf, dev):
+    """Launches of the plain copy kernel on a buffer of known size (profiler calibration)."""
+    x = torch.ones(COPY_ELEMS, dtype=torch.float32, device=dev)
+    for _ in range(args.warmup):
+        mtf.cast(x, torch.float32)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        y = mtf.cast(x, torch.float32)
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / args.steps
+    ok = bool((y[:: 1 << 16] == 1).all().item())
+    print(json.dumps({"metric": "copy kernel (profiler calibration, not the hot path)", "kernel": "cast_kernel",
+                      "bytes_read_per_launch": COPY_ELEMS * 4, "bytes_written_per_launch": COPY_ELEMS * 4,
+                      "value": round(2 * COPY_ELEMS * 4 / dt / 1e9, 1), "unit": "GB/s", "steps": args.steps,
+                      "warmup": args.warmup, "copied_correctly": ok}))
+    return 0 if ok else 1
+
+
+def measured_traffic(workload, kernel):
+    """HBM bytes per launch of `kernel`, from the committed rocprofv3 --pmc summary (FETCH_SIZE and
+    WRITE_SIZE runs scaled by the same counters on the copy kernel), or None if that summary is
+    for another kernel or workload."""
+    path = os.path.join(ROOT, "profiles", "dominant_kernel_hbm_traffic.txt")
+    try:
+        fields = {}
+        for line in open(path):
+            if "=" in line and not line.lstrip().startswith("#"):
+                k, v = line.split("=", 1)
+                fields[k.strip()] = v.strip()
+        if fields.get("workload") != workload or fields.get("kernel") != kernel:
+            return None
+        return float(fields["traffic_bytes_per_launch"])
+    except (OSError, KeyError, ValueError):
+        return None
 
 
 def cpu_baseline(workload, cfg):
