@@ -38,7 +38,7 @@ struct AttnArgs {
   const bf16_t *q, *k, *v, *ctx, *dctx;
   bf16_t *out0, *out1;  // fwd: ctx | dq kernel: dq | dkv kernel: dk, dv
   const float *lse_in, *delta_in;
-  float* lse_out;
+  float *lse_out, *delta_out;
   int batch, length, heads;
   float scale;
   int causal;
@@ -338,34 +338,9 @@ __global__ void __launch_bounds__(NWAVES * 64, 2) attn_fwd_kernel(AttnArgs a) {
 }
 
 // ------------------------------------------------------------------------------------ backward
-// delta[b,h,l] = sum_d dctx[b,l,h,d] * ctx[b,l,h,d]  (= sum_m p * dp of the softmax Jacobian)
-__global__ void __launch_bounds__(256) attn_delta_kernel(const bf16_t* __restrict__ ctx,
-                                                        const bf16_t* __restrict__ dctx,
-                                                        float* __restrict__ delta, int batch,
-                                                        int length, int heads) {
-  const int64_t rows = (int64_t)batch * length * heads;  // (b, l, h) in memory order
-  const int64_t row = blockIdx.x * 16 + (threadIdx.x >> 4);
-  const int sub = threadIdx.x & 15;
-  float acc = 0.f;
-  if (row < rows) {
-    const uint4 x = *reinterpret_cast<const uint4*>(ctx + row * kHeadDim + sub * 8);
-    const uint4 y = *reinterpret_cast<const uint4*>(dctx + row * kHeadDim + sub * 8);
-    const uint32_t xs[4] = {x.x, x.y, x.z, x.w}, ys[4] = {y.x, y.y, y.z, y.w};
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      acc = fmaf(__uint_as_float(xs[i] << 16), __uint_as_float(ys[i] << 16), acc);
-      acc = fmaf(__uint_as_float(xs[i] & 0xffff0000u), __uint_as_float(ys[i] & 0xffff0000u), acc);
-    }
-  }
-#pragma unroll
-  for (int m = 8; m >= 1; m >>= 1) acc += __shfl_xor(acc, m);
-  if (row < rows && sub == 0) {
-    const int64_t h = row % heads, l = (row / heads) % length, b = row / ((int64_t)heads * length);
-    delta[(b * heads + h) * length + l] = acc;
-  }
-}
-
-// dq: one workgroup per NWAVES*32 query rows; loops over memory tiles.
+// dq: one workgroup per NWAVES*32 query rows; loops over memory tiles.  Also produces
+// delta[b,h,l] = sum_d dctx[b,l,h,d] * ctx[b,l,h,d] (= sum_m p * dp of the softmax Jacobian) for
+// its rows, which the dk/dv kernel launched after it reads.
 template <int NWAVES>
 __global__ void __launch_bounds__(NWAVES * 64, 2) attn_dq_kernel(AttnArgs a) {
   __shared__ __attribute__((aligned(1024))) char stage0[2 * kTileBytes];  // K tile, V tile
@@ -389,7 +364,26 @@ __global__ void __launch_bounds__(NWAVES * 64, 2) attn_dq_kernel(AttnArgs a) {
     dof[ks] = global_rows_frag(dob, rs, q_load, ks, lane);
   }
   const int64_t stat = ((int64_t)b * H + h) * L + q_load;
-  float lse2 = a.lse_in[stat] * kLog2e, dls = a.delta_in[stat] * a.scale;
+  float lse2 = a.lse_in[stat] * kLog2e;
+  // this lane holds 64 of its row's 128 d (the lane 32 further on holds the rest)
+  float delta = 0.f;
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) {
+    union {
+      bf16x8 v;
+      uint32_t w[4];
+    } o, g;
+    o.v = global_rows_frag(a.ctx + head0, rs, q_load, ks, lane);
+    g.v = dof[ks];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      delta = fmaf(__uint_as_float(o.w[i] << 16), __uint_as_float(g.w[i] << 16), delta);
+      delta = fmaf(__uint_as_float(o.w[i] & 0xffff0000u), __uint_as_float(g.w[i] & 0xffff0000u), delta);
+    }
+  }
+  delta += __shfl_xor(delta, 32);
+  if (qr.active && q_lane < L && hf == 0) a.delta_out[stat] = delta;
+  float dls = delta * a.scale;
   const float c2 = a.scale * kLog2e;
 #pragma unroll
   for (int ks = 0; ks < 8; ++ks) {
@@ -680,23 +674,17 @@ int attn_bwd_launch(const AttnShape& s, const bf16_t* q, const bf16_t* k, const 
                     const bf16_t* ctx, const float* lse, const bf16_t* dctx, bf16_t* dq, bf16_t* dk,
                     bf16_t* dv, float* delta, hipStream_t stream) {
   if (int rc = check_shape(s)) return rc;
-  const int64_t rows = (int64_t)s.batch * s.length * s.heads;
   const double pairs = s.causal ? 0.5 * s.length * (s.length + 1.0) : (double)s.length * s.length;
   const double unit = 2.0 * s.batch * s.heads * pairs * kHeadDim;  // one contraction over visible pairs
   const double act = (double)s.batch * s.length * s.heads * kRowBytes;
-  {
-    LaunchTimer timer("attn_delta_kernel", 0, 2.0 * act, stream);
-    attn_delta_kernel<<<(unsigned)ceil_div(rows, 16), 256, 0, stream>>>(ctx, dctx, delta, s.batch, s.length, s.heads);
-  }
-  if (int rc = launch_status("attn_delta_kernel")) return rc;
   AttnArgs a = make_args(s);
-  a.q = q; a.k = k; a.v = v; a.dctx = dctx; a.lse_in = lse; a.delta_in = delta;
+  a.q = q; a.k = k; a.v = v; a.ctx = ctx; a.dctx = dctx; a.lse_in = lse; a.delta_in = delta; a.delta_out = delta;
   {  // dq = einsum(ds, k): 1 of the 4 backward contractions (the recomputed logits and dp are overhead here)
     const int nw = waves_per_group(s, 8);
     dim3 grid((unsigned)s.heads, (unsigned)s.batch, (unsigned)ceil_div(s.length, nw * 32));
     a.out0 = dq;
     LaunchTimer timer(nw == 8 ? "attn_dq_kernel<8>" : nw == 4 ? "attn_dq_kernel<4>" : "attn_dq_kernel<2>", unit,
-                      5.0 * act, stream);
+                      6.0 * act, stream);
     if (nw == 8)
       attn_dq_kernel<8><<<grid, 512, 0, stream>>>(a);
     else if (nw == 4)
