@@ -152,22 +152,56 @@ __device__ __forceinline__ f32x16 zero16() {
 // Row of an accumulator value: value jj of a lane in half hf sits at row (jj/4)*8 + hf*4 + jj%4.
 __device__ __forceinline__ int acc_row(int jj, int hf) { return (jj >> 2) * 8 + hf * 4 + (jj & 3); }
 
+// A slab = 32 rows of 256 B private to one wave, same chunk swizzle as a tile.  The fragments a
+// wave keeps in registers for the whole kernel, and the rows it stores at the end, pass through
+// it so that global memory sees whole 256-byte rows (a fragment taken straight from global
+// memory is 32-byte pieces of 32 different rows per instruction).
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+constexpr int kSlabBytes = 32 * kRowBytes;  // 8 KiB
+
+// slab <- rows row0 .. row0+31 (clamped to row_limit-1); asynchronous, completes with the wave's
+// other tile loads (s_waitcnt vmcnt).
+__device__ __forceinline__ void load_slab(const bf16_t* base, uint32_t row_stride_bytes, int row0,
+                                          int row_limit, char* slab, int lane) {
+#pragma unroll
+  for (int run = 0; run < 8; ++run) {
+    const int row = run * 4 + (lane >> 4);
+    const int c = (lane & 15) ^ swz(row);
+    const int src = min(row0 + row, row_limit - 1);
+    load16_to_lds(reinterpret_cast<const char*>(base), (uint32_t)src * row_stride_bytes + c * 16,
+                  lds_address(slab) + run * 1024);
+  }
+}
+
 // Stores a [32 x 128]^T accumulator set (lane = one row of the output, 4 consecutive d per group)
-// as bf16 rows of a [*, rows, heads, 128] tensor.
-__device__ __forceinline__ void store_rows_bf16(bf16_t* base, int64_t row_stride, int row,
+// as bf16 rows row0 .. row0+31 (those below row_limit) of a [*, rows, heads, 128] tensor.  Only
+// this wave touches `slab`.
+__device__ __forceinline__ void store_rows_bf16(bf16_t* base, int64_t row_stride, int row0,
                                                 int row_limit, const f32x16* acc, float mul,
-                                                int lane) {
-  if (row >= row_limit) return;
-  const int hf = lane >> 5;
+                                                char* slab, int lane) {
+  // keeps the compiler from preparing the addresses of these stores before the tile loop and
+  // carrying them through it in registers it does not have
+  asm volatile("" : "+v"(lane));
+  const int hf = lane >> 5, r = lane & 31;
 #pragma unroll
   for (int blk = 0; blk < 4; ++blk)
 #pragma unroll
     for (int q4 = 0; q4 < 4; ++q4) {
       const int d = blk * 32 + q4 * 8 + hf * 4;
-      uint2 w = make_uint2(pack_bf16x2(acc[blk][q4 * 4 + 0] * mul, acc[blk][q4 * 4 + 1] * mul),
-                           pack_bf16x2(acc[blk][q4 * 4 + 2] * mul, acc[blk][q4 * 4 + 3] * mul));
-      *reinterpret_cast<uint2*>(base + (int64_t)row * row_stride + d) = w;
+      u32x2 w;
+      w[0] = pack_bf16x2(acc[blk][q4 * 4 + 0] * mul, acc[blk][q4 * 4 + 1] * mul);
+      w[1] = pack_bf16x2(acc[blk][q4 * 4 + 2] * mul, acc[blk][q4 * 4 + 3] * mul);
+      *LDS_PTR(u32x2, slab + r * kRowBytes + (((d >> 3) ^ swz(r)) << 4) + (d & 7) * 2) = w;
     }
+  __builtin_amdgcn_wave_barrier();  // LDS operations of a wave complete in order
+#pragma unroll
+  for (int run = 0; run < 8; ++run) {
+    const int row = run * 4 + (lane >> 4), c = lane & 15;
+    const u32x4 v = *LDS_PTR(const u32x4, slab + row * kRowBytes + ((c ^ swz(row)) << 4));
+    if (row0 + row < row_limit)
+      *reinterpret_cast<u32x4*>(base + (int64_t)(row0 + row) * row_stride + c * 8) = v;
+  }
 }
 
 // Query rows of a workgroup.  With 8 waves the workgroup takes two blocks of 128 query rows, one
@@ -205,8 +239,14 @@ template <int NWAVES>
 __global__ void __launch_bounds__(NWAVES * 64, 2) attn_fwd_kernel(AttnArgs a) {
   __shared__ __attribute__((aligned(1024))) char stage0[2 * kTileBytes];  // K tile, V tile
   __shared__ __attribute__((aligned(1024))) char stage1[2 * kTileBytes];
+  // Slabs: with 8 waves they need as much LDS as both stages, and get their own (one workgroup
+  // per CU either way); smaller workgroups borrow stage 1, which the pipeline first writes at
+  // the barrier of step 0 and last reads before the barrier that precedes the final stores.
+  constexpr bool kOwnSlabs = NWAVES == 8;
+  __shared__ __attribute__((aligned(1024))) char slabs[kOwnSlabs ? NWAVES * kSlabBytes : 16];
   const int lane = threadIdx.x & 63, hf = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  char* slab = (kOwnSlabs ? slabs : stage1) + wave * kSlabBytes;
   const int L = a.length, H = a.heads;
   const int b = blockIdx.y, h = blockIdx.x;
   const QueryRows qr = query_rows<NWAVES>(L, a.causal, wave);
@@ -216,12 +256,19 @@ __global__ void __launch_bounds__(NWAVES * 64, 2) attn_fwd_kernel(AttnArgs a) {
   const bf16_t *qb = a.q + head0, *kb = a.k + head0, *vb = a.v + head0;
 
   const int q_lane = q0w + (lane & 31);  // this lane's query row
-  const int q_load = min(q_lane, L - 1);
+  const int kv_end = a.causal ? min(L, qr.last_row + 1) : L;
+  const int n_tiles = (kv_end + kTileRows - 1) / kTileRows;
+  auto issue = [&](int t, char* st) {
+    load_tile<NWAVES>(kb, (uint32_t)(rs * 2), t * kTileRows, L, st, wave, lane);
+    load_tile<NWAVES>(vb, (uint32_t)(rs * 2), t * kTileRows, L, st + kTileBytes, wave, lane);
+  };
+  // this wave's query rows and the first K/V tile travel together
+  load_slab(qb, (uint32_t)(rs * 2), q0w, L, slab, lane);
+  issue(0, stage0);
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * (16 / NWAVES)) : "memory");  // the slab has landed
   bf16x8 qf[8];
 #pragma unroll
-  for (int ks = 0; ks < 8; ++ks) qf[ks] = global_rows_frag(qb, rs, q_load, ks, lane);
-#pragma unroll
-  for (int ks = 0; ks < 8; ++ks) settle(qf[ks]);
+  for (int ks = 0; ks < 8; ++ks) qf[ks] = rows_frag(slab, 0, ks, lane);
   // The running maximum works on s * c with c >= 0.  A negative scale is moved into q (sign
   // bits flipped: logits come out negated); a zero scale becomes a tiny positive one (logits
   // of order 1e-30 instead of 0), which keeps -inf * c = -inf for hidden positions.
@@ -245,12 +292,6 @@ __global__ void __launch_bounds__(NWAVES * 64, 2) attn_fwd_kernel(AttnArgs a) {
   float m2 = -INFINITY, lsum = 0.f;  // running max (log2 units) and row sum
   const float c2 = fmaxf(fabsf(a.scale) * kLog2e, 1e-30f);
 
-  const int kv_end = a.causal ? min(L, qr.last_row + 1) : L;
-  const int n_tiles = (kv_end + kTileRows - 1) / kTileRows;
-  auto issue = [&](int t, char* st) {
-    load_tile<NWAVES>(kb, (uint32_t)(rs * 2), t * kTileRows, L, st, wave, lane);
-    load_tile<NWAVES>(vb, (uint32_t)(rs * 2), t * kTileRows, L, st + kTileBytes, wave, lane);
-  };
   auto process = [&](int t, const char* st) {
     const int kv0 = t * kTileRows;
     const char *kt_ = st, *vt_ = st + kTileBytes;
@@ -323,7 +364,6 @@ __global__ void __launch_bounds__(NWAVES * 64, 2) attn_fwd_kernel(AttnArgs a) {
   };
   // Two stages: the tile after the one being processed is in flight.  Passing the barrier means
   // everyone has the current tile and is done with the stage the next issue() overwrites.
-  issue(0, stage0);
   for (int t = 0; t < n_tiles; ++t) {
     char* cur = (t & 1) ? stage1 : stage0;
     char* nxt = (t & 1) ? stage0 : stage1;
@@ -331,8 +371,9 @@ __global__ void __launch_bounds__(NWAVES * 64, 2) attn_fwd_kernel(AttnArgs a) {
     if (t + 1 < n_tiles) issue(t + 1, nxt);
     process(t, cur);
   }
+  if (!kOwnSlabs) __syncthreads();  // stage 1 may still be read by a slower wave
   if (!qr.active) return;
-  store_rows_bf16(a.out0 + head0, rs, q_lane, L, o, 1.f / lsum, lane);
+  store_rows_bf16(a.out0 + head0, rs, q0w, L, o, 1.f / lsum, slab, lane);
   if (q_lane < L && hf == 0)
     a.lse_out[((int64_t)b * H + h) * L + q_lane] = (m2 + __log2f(lsum)) * kLn2;
 }
@@ -345,8 +386,11 @@ template <int NWAVES>
 __global__ void __launch_bounds__(NWAVES * 64, 2) attn_dq_kernel(AttnArgs a) {
   __shared__ __attribute__((aligned(1024))) char stage0[2 * kTileBytes];  // K tile, V tile
   __shared__ __attribute__((aligned(1024))) char stage1[2 * kTileBytes];
+  constexpr bool kOwnSlabs = NWAVES == 8;  // as in the forward kernel
+  __shared__ __attribute__((aligned(1024))) char slabs[kOwnSlabs ? NWAVES * kSlabBytes : 16];
   const int lane = threadIdx.x & 63, hf = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  char* slab = (kOwnSlabs ? slabs : stage1) + wave * kSlabBytes;
   const int L = a.length, H = a.heads;
   const int b = blockIdx.y, h = blockIdx.x;
   const QueryRows qr = query_rows<NWAVES>(L, a.causal, wave);
@@ -357,15 +401,31 @@ __global__ void __launch_bounds__(NWAVES * 64, 2) attn_dq_kernel(AttnArgs a) {
 
   const int q_lane = q0w + (lane & 31);
   const int q_load = min(q_lane, L - 1);
-  bf16x8 qf[8], dof[8];
-#pragma unroll
-  for (int ks = 0; ks < 8; ++ks) {
-    qf[ks] = global_rows_frag(qb, rs, q_load, ks, lane);
-    dof[ks] = global_rows_frag(dob, rs, q_load, ks, lane);
-  }
+  const int kv_end = a.causal ? min(L, qr.last_row + 1) : L;
+  const int n_tiles = (kv_end + kTileRows - 1) / kTileRows;
+  auto issue = [&](int t, char* st) {
+    load_tile<NWAVES>(kb, (uint32_t)(rs * 2), t * kTileRows, L, st, wave, lane);
+    load_tile<NWAVES>(vb, (uint32_t)(rs * 2), t * kTileRows, L, st + kTileBytes, wave, lane);
+  };
   const int64_t stat = ((int64_t)b * H + h) * L + q_load;
   float lse2 = a.lse_in[stat] * kLog2e;
-  // this lane holds 64 of its row's 128 d (the lane 32 further on holds the rest)
+  settle(lse2);  // before any asynchronous load is in flight
+  // This wave's rows of dctx, then of q, pass through its slab; the ctx rows (used once, for
+  // delta) come straight from global memory alongside the dctx slab and the first K/V tile.
+  bf16x8 qf[8], dof[8], of[8];
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) of[ks] = global_rows_frag(a.ctx + head0, rs, q_load, ks, lane);
+  load_slab(dob, (uint32_t)(rs * 2), q0w, L, slab, lane);
+  issue(0, stage0);
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * (16 / NWAVES)) : "memory");  // ctx rows and slab have landed
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) {
+    settle(of[ks]);
+    dof[ks] = rows_frag(slab, 0, ks, lane);
+  }
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // fragments read before the slab is overwritten
+  load_slab(qb, (uint32_t)(rs * 2), q0w, L, slab, lane);
+  // delta: this lane holds 64 of its row's 128 d (the lane 32 further on holds the rest)
   float delta = 0.f;
 #pragma unroll
   for (int ks = 0; ks < 8; ++ks) {
@@ -373,7 +433,7 @@ __global__ void __launch_bounds__(NWAVES * 64, 2) attn_dq_kernel(AttnArgs a) {
       bf16x8 v;
       uint32_t w[4];
     } o, g;
-    o.v = global_rows_frag(a.ctx + head0, rs, q_load, ks, lane);
+    o.v = of[ks];
     g.v = dof[ks];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -383,26 +443,16 @@ __global__ void __launch_bounds__(NWAVES * 64, 2) attn_dq_kernel(AttnArgs a) {
   }
   delta += __shfl_xor(delta, 32);
   if (qr.active && q_lane < L && hf == 0) a.delta_out[stat] = delta;
-  float dls = delta * a.scale;
+  const float dls = delta * a.scale;
   const float c2 = a.scale * kLog2e;
+  wait_loads();
 #pragma unroll
-  for (int ks = 0; ks < 8; ++ks) {
-    settle(qf[ks]);
-    settle(dof[ks]);
-  }
-  settle(lse2);
-  settle(dls);
+  for (int ks = 0; ks < 8; ++ks) qf[ks] = rows_frag(slab, 0, ks, lane);
 
   f32x16 dq[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) dq[i] = zero16();
 
-  const int kv_end = a.causal ? min(L, qr.last_row + 1) : L;
-  const int n_tiles = (kv_end + kTileRows - 1) / kTileRows;
-  auto issue = [&](int t, char* st) {
-    load_tile<NWAVES>(kb, (uint32_t)(rs * 2), t * kTileRows, L, st, wave, lane);
-    load_tile<NWAVES>(vb, (uint32_t)(rs * 2), t * kTileRows, L, st + kTileBytes, wave, lane);
-  };
   auto process = [&](int t, const char* st) {
     const int kv0 = t * kTileRows;
     const char *kt_ = st, *vt_ = st + kTileBytes;
@@ -441,7 +491,6 @@ __global__ void __launch_bounds__(NWAVES * 64, 2) attn_dq_kernel(AttnArgs a) {
         dq[blk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cols_frag(kt_, blk * 32, t * 16, lane), dsf[t],
                                                           dq[blk], 0, 0, 0);
   };
-  issue(0, stage0);
   for (int t = 0; t < n_tiles; ++t) {
     char* cur = (t & 1) ? stage1 : stage0;
     char* nxt = (t & 1) ? stage0 : stage1;
@@ -449,8 +498,9 @@ __global__ void __launch_bounds__(NWAVES * 64, 2) attn_dq_kernel(AttnArgs a) {
     if (t + 1 < n_tiles) issue(t + 1, nxt);
     process(t, cur);
   }
+  if (!kOwnSlabs) __syncthreads();  // stage 1 may still be read by a slower wave
   if (!qr.active) return;
-  store_rows_bf16(a.out0 + head0, rs, q_lane, L, dq, 1.f, lane);
+  store_rows_bf16(a.out0 + head0, rs, q0w, L, dq, 1.f, slab, lane);
 }
 
 // dk, dv: one workgroup per NWAVES*32 memory rows; loops over query tiles.
@@ -460,8 +510,16 @@ __global__ void __launch_bounds__(NWAVES * 64, 1) attn_dkv_kernel(AttnArgs a) {
   __shared__ __attribute__((aligned(1024))) char stage1[2 * kTileBytes];
   __shared__ __attribute__((aligned(16))) float stats0[2 * kTileRows];  // lse * log2(e), delta
   __shared__ __attribute__((aligned(16))) float stats1[2 * kTileRows];
+  // Two slabs per wave (its K rows, its V rows; later its dk and dv rows).  The 4-wave kernel
+  // gives them LDS of their own (registers allow one workgroup per CU anyway); the 2-wave kernel
+  // borrows stage 1, which the pipeline first writes at the barrier of its first step and last
+  // reads before the barrier that precedes the final stores.
+  constexpr bool kOwnSlabs = NWAVES == 4;
+  __shared__ __attribute__((aligned(1024))) char slabs[kOwnSlabs ? NWAVES * 2 * kSlabBytes : 16];
   const int lane = threadIdx.x & 63, hf = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  char* slab_k = (kOwnSlabs ? slabs : stage1) + wave * 2 * kSlabBytes;
+  char* slab_v = slab_k + kSlabBytes;
   const int L = a.length, H = a.heads;
   const int b = blockIdx.y, h = blockIdx.x;
   const int kvblk0 = blockIdx.z * (NWAVES * 32);  // causal: early memory rows are seen by more queries
@@ -471,19 +529,9 @@ __global__ void __launch_bounds__(NWAVES * 64, 1) attn_dkv_kernel(AttnArgs a) {
   const float* lse_row = a.lse_in + ((int64_t)b * H + h) * L;
   const float* delta_row = a.delta_in + ((int64_t)b * H + h) * L;
 
-  const int kv_lane = kvblk0 + wave * 32 + (lane & 31);  // this lane's memory row
-  const int kv_load = min(kv_lane, L - 1);
-  bf16x8 kf[8], vf[8];
-#pragma unroll
-  for (int ks = 0; ks < 8; ++ks) {
-    kf[ks] = global_rows_frag(kb, rs, kv_load, ks, lane);
-    vf[ks] = global_rows_frag(vb, rs, kv_load, ks, lane);
-  }
-#pragma unroll
-  for (int ks = 0; ks < 8; ++ks) {
-    settle(kf[ks]);
-    settle(vf[ks]);
-  }
+  const int kv_row0 = kvblk0 + wave * 32;                // this wave's memory rows
+  const int kv_lane = kv_row0 + (lane & 31);             // this lane's memory row
+  bf16x8 kf[8], vf[8];                                   // its K and V fragments, set before the tile loop
   const float c2 = a.scale * kLog2e;
   f32x16 dk[4], dv[4];
 #pragma unroll
@@ -597,7 +645,16 @@ __global__ void __launch_bounds__(NWAVES * 64, 1) attn_dkv_kernel(AttnArgs a) {
       __builtin_amdgcn_sched_barrier(0);
     }
   };
+  // this wave's K and V rows and the first Q/dO tile travel together
+  load_slab(kb, (uint32_t)(rs * 2), kv_row0, L, slab_k, lane);
+  load_slab(vb, (uint32_t)(rs * 2), kv_row0, L, slab_v, lane);
   issue(t_begin, stage0);
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * (16 / NWAVES)) : "memory");  // both slabs have landed
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) {
+    kf[ks] = rows_frag(slab_k, 0, ks, lane);
+    vf[ks] = rows_frag(slab_v, 0, ks, lane);
+  }
   for (int t = t_begin; t < t_end; t += 2) {
     wait_loads();
     commit_stats(stats0);
@@ -611,8 +668,9 @@ __global__ void __launch_bounds__(NWAVES * 64, 1) attn_dkv_kernel(AttnArgs a) {
     if (t + 2 < t_end) issue(t + 2, stage0);
     process(t + 1, stage1, stats1);
   }
-  store_rows_bf16(a.out0 + head0, rs, kv_lane, L, dk, 1.f, lane);
-  store_rows_bf16(a.out1 + head0, rs, kv_lane, L, dv, 1.f, lane);
+  if (!kOwnSlabs) __syncthreads();  // stage 1 may still be read by a slower wave
+  store_rows_bf16(a.out0 + head0, rs, kv_row0, L, dk, 1.f, slab_k, lane);
+  store_rows_bf16(a.out1 + head0, rs, kv_row0, L, dv, 1.f, slab_v, lane);
 }
 
 int check_shape(const AttnShape& s) {
