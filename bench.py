@@ -74,9 +74,15 @@ def main():
         w = {k: g[k] for k in ("w_q", "w_k", "w_v", "w_o", "w_in", "w_out")}
         bufs = mtf.layer_alloc(g["x"], w)
 
-        def step():
+        def step_fwd():
             mtf.layer_fwd(g["x"], w, cfg["scale"], causal, bufs)
+
+        def step_bwd():
             mtf.layer_bwd(g["x"], w, bufs["saved"], g["dz"], cfg["scale"], causal, bufs)
+
+        def step():
+            step_fwd()
+            step_bwd()
     elif args.workload == "ffn":
         cfg = mtf_inputs.config2()
         B, L, D = cfg["x"].shape
@@ -116,13 +122,32 @@ def main():
     ms_per_step = elapsed * 1e3 / args.steps
     tflops = step_flops / (ms_per_step * 1e-3) / 1e12
 
+    # ---------------------------------------------------------------- forward / backward split
+    halves = None
+    if args.workload == "layer":
+        ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+        for e in ev:                     # the binding launches on torch's current stream
+            e[0].record(); step_fwd(); e[1].record(); step_bwd(); e[2].record()
+        torch.cuda.synchronize()
+        f = sorted(e[0].elapsed_time(e[1]) for e in ev)
+        b = sorted(e[1].elapsed_time(e[2]) for e in ev)
+        halves = {"fwd_ms_median": round(f[len(f) // 2], 4), "fwd_ms_min": round(f[0], 4),
+                  "bwd_ms_median": round(b[len(b) // 2], 4), "bwd_ms_min": round(b[0], 4)}
+
     # ---------------------------------------------------------------- dominant kernel, timed per launch
     # same steps again with every launch bracketed by HIP events on the launch stream
     mtf.timing_enable(True)
     for _ in range(args.steps):
         step()
     kinds = mtf.timing_collect()
+    # what the matrix cores alone sustain here, operands distributed like the path's (N(0,1) bf16)
+    ops = mtf_inputs.normal(0, 99, (4096,)).to(torch.bfloat16).to(dev)
+    sink = torch.empty(64, dtype=torch.float32, device=dev)
+    for _ in range(12):                  # ~0.6 ms each: long enough for the clock to settle
+        mtf.mfma_ceiling(ops, 2000, sink)
+    ceil = [r for r in mtf.timing_collect() if r["kernel"] == "mfma_ceiling_kernel"]
     mtf.timing_enable(False)
+    mfma_only = round(ceil[0]["flops"] / (ceil[0]["total_ms"] * 1e-3) / 1e12, 1) if ceil else None
     kinds.sort(key=lambda r: -r["total_ms"])
     dom = kinds[0]
     avg_ms = dom["total_ms"] / dom["launches"]
@@ -131,7 +156,7 @@ def main():
                     frac=round(achieved / PEAK_BF16_TFLOPS, 4),
                     traffic=measured_traffic(args.workload, dom["kernel"]),
                     kernel=dom["kernel"], launches_per_step=dom["launches"] // args.steps,
-                    avg_launch_us=round(avg_ms * 1e3, 2))
+                    avg_launch_us=round(avg_ms * 1e3, 2), mfma_only_measured_tflops=mfma_only)
     all_ms = sum(r["total_ms"] for r in kinds)
     gemm = [r for r in kinds if r["kernel"].startswith("gemm_bf16_kernel")]
     breakdown = {r["kernel"]: dict(us_per_step=round(r["total_ms"] * 1e3 / args.steps, 1),
@@ -156,6 +181,7 @@ def main():
         "frac_of_bf16_mfma_peak": round(tflops / PEAK_BF16_TFLOPS, 4),
         "roofline": roofline,
         "cpu_baseline": cpu,
+        "fwd_bwd": halves,
         "kernels": breakdown,
         "all_gemm_launches_tflops": round(gemm_tflops, 1) if gemm_tflops else None,
         "kernel_time_ms_per_step": round(all_ms / args.steps, 4),

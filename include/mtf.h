@@ -243,6 +243,16 @@ int mtf_timing_enable(int on);
 /* out: host array of max_kinds entries; *n_kinds receives the number filled. */
 int mtf_timing_collect(mtf_kernel_time* out, int32_t max_kinds, int32_t* n_kinds);
 
+/* What the matrix cores alone sustain on this device, for the roofline a contraction is held
+ * against: one launch of a kernel that does nothing but v_mfma_f32_32x32x16_bf16 (8 independent
+ * accumulators per wavefront, 8 wavefronts per CU on every CU), operands taken from `operands`
+ * (device, bf16, at least 4096 elements; power draw, hence the sustained clock, depends on the
+ * operand bits: pass values distributed like the real operands).  `iters` MFMAs per accumulator
+ * (> 0).  `sink` (device, at least 64 floats) receives a value derived from the accumulators so
+ * the loop is not optimised away.  *flops receives the FLOP of the launch (host).  Time it with
+ * events or with mtf_timing_*: kernel name "mfma_ceiling_kernel". */
+int mtf_mfma_ceiling(const void* operands, int32_t iters, void* sink, double* flops, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -373,6 +373,13 @@ class mtf_kernel_time(C.Structure):
                 ("flops", C.c_double), ("bytes", C.c_double)]
 
 
+def mfma_ceiling(operands, iters, sink):
+    """One launch of the MFMA-only kernel; returns the FLOP it performs."""
+    flops = C.c_double()
+    _check(lib.mtf_mfma_ceiling(_ptr(operands), C.c_int32(iters), _ptr(sink), C.byref(flops), _stream()))
+    return flops.value
+
+
 def timing_enable(on):
     _check(lib.mtf_timing_enable(1 if on else 0))
 

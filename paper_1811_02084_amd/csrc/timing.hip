@@ -59,7 +59,65 @@ LaunchTimer::~LaunchTimer() {
 
 using namespace mtf;
 
+namespace {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
+
+// Nothing but MFMAs: 8 independent accumulators per wave, 4 A and 4 B fragments in rotation so
+// that consecutive instructions see different operand bits, as they do in a contraction.
+__global__ void __launch_bounds__(256, 2) mfma_ceiling_kernel(const uint16_t* __restrict__ operands, int iters,
+                                                             float* __restrict__ sink) {
+  const int lane = threadIdx.x & 63;
+  bf16x8_t a[4], b[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    a[i] = *reinterpret_cast<const bf16x8_t*>(operands + (i * 64 + lane) * 8);
+    b[i] = *reinterpret_cast<const bf16x8_t*>(operands + 2048 + (i * 64 + lane) * 8);
+  }
+  f32x16_t acc[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[i][e] = 0.f;
+  for (int it = 0; it < iters; it += 4) {  // 4 rounds per trip keep every register index static
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+#pragma unroll
+      for (int i = 0; i < 8; ++i)
+        acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i & 3], b[(i + r) & 3], acc[i], 0, 0, 0);
+  }
+  float total = 0.f;
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) total += acc[i][e];
+  if (blockIdx.x == 0 && threadIdx.x < 64) sink[threadIdx.x] = total;
+}
+
+}  // namespace
+
 extern "C" {
+
+int mtf_mfma_ceiling(const void* operands, int32_t iters, void* sink, double* flops, void* stream) {
+  if (!operands || !sink || !flops) return fail(MTF_ERR_NULL, "operands / sink / flops");
+  if (iters <= 0) return fail(MTF_ERR_SIZE_MISMATCH, "iters %d", iters);
+  if (!aligned16(operands)) return fail(MTF_ERR_ALIGN, "operands");
+  hipDeviceProp_t prop;
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess)
+    return fail(MTF_ERR_HIP, "device properties");
+  const int groups = prop.multiProcessorCount * 2;  // 2 workgroups of 4 waves per CU
+  const int rounds = (iters + 3) / 4 * 4;  // the kernel runs whole trips of 4
+  *flops = 2.0 * 32 * 32 * 16 * 8.0 * rounds * 4.0 * groups;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  {
+    LaunchTimer timer("mfma_ceiling_kernel", *flops, 0, s);
+    mfma_ceiling_kernel<<<groups, 256, 0, s>>>(static_cast<const uint16_t*>(operands), iters,
+                                              static_cast<float*>(sink));
+  }
+  return launch_status("mfma_ceiling_kernel");
+}
 
 int mtf_timing_enable(int on) {
   std::lock_guard<std::mutex> lock(g_mu);
