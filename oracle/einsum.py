@@ -12,6 +12,10 @@ shape is summed out.  Dimensions are identified by NAME; a tensor is a pair
                       numpy's own einsum in fp64 (a library primitive as one step)
   einsum_abs          the same contraction of absolute values (denominator of the
                       forward-error measure M1)
+  reduce              reduce_sum / reduce_max: the output dims are a subset of the input
+                      dims ("Operation Implementation", paragraph "Reduction")
+  add_broadcast       component-wise addition with implicit broadcasting of the operand
+                      whose shape is a subset of the other's ("Mesh-TensorFlow syntax")
 """
 from collections import namedtuple
 import string
@@ -21,7 +25,7 @@ NT = namedtuple("NT", ["data", "dims"])       # named tensor: ndarray + tuple of
 
 
 class EinsumError(ValueError):
-    """code is one of DUP_DIM, SIZE_MISMATCH, OUT_NOT_SUBSET."""
+    """code is one of DUP_DIM, SIZE_MISMATCH, OUT_NOT_SUBSET, NOT_BROADCASTABLE."""
 
     def __init__(self, code, msg=""):
         super().__init__(f"{code}: {msg}")
@@ -112,3 +116,34 @@ def flops(inputs):
     for n in union_dims(inputs).values():
         space *= n
     return 2 * space
+
+
+def reduce(t, out_dims, op="sum"):
+    """Reduction whose output dims are a subset of the input dims: every other dim is summed
+    (op="sum") or maximised (op="max") out; the result is laid out in out_dims order."""
+    sizes = union_dims([t])
+    out_dims = _check_out(sizes, out_dims)
+    gone = tuple(i for i, d in enumerate(t.dims) if d not in out_dims)
+    if op == "sum":
+        res = t.data.sum(axis=gone) if gone else np.array(t.data)
+    elif op == "max":
+        res = t.data.max(axis=gone) if gone else np.array(t.data)
+    else:
+        raise ValueError(op)
+    kept = [d for d in t.dims if d in out_dims]
+    res = np.transpose(res, [kept.index(d) for d in out_dims])
+    return NT(np.array(res, dtype=np.float64, order="C"), out_dims)
+
+
+def add_broadcast(a, b):
+    """a + b where the dims of one operand are a subset of the other's: the smaller operand is
+    repeated along the dims it lacks.  The result has the larger operand's dims, in its order."""
+    sizes = union_dims([a, b])
+    big, small = (a, b) if len(a.dims) >= len(b.dims) else (b, a)
+    if not set(small.dims) <= set(big.dims):
+        raise EinsumError("NOT_BROADCASTABLE", f"{a.dims} + {b.dims}")
+    # the small operand's axes in the order they occur in the big one, size 1 elsewhere
+    order = sorted(range(len(small.dims)), key=lambda ax: big.dims.index(small.dims[ax]))
+    arr = np.transpose(small.data, order)
+    shape = [sizes[d] if d in small.dims else 1 for d in big.dims]
+    return NT(np.array(big.data + arr.reshape(shape), dtype=np.float64, order="C"), big.dims)

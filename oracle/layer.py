@@ -7,7 +7,7 @@ W_out[d_ff/n, d_model], W_{q,k,v}[d_model, heads/n, d_k] and W_o[heads/n, d_v, d
 its outputs y (and dx in backward) contract the split dim and are therefore PARTIAL sums
 that the lowering would Allreduce ("Operation Implementation", einsum paragraph; worked
 example, "Model-Parallel Layout").  The feed-forward sublayer is the worked example
-y = Relu(x w) v without its bias.  Gradients of einsums are einsums ("Data-Parallel
+y = Relu(x w) v without its bias; ffn_bias_* are the example as printed, with it.  Gradients of einsums are einsums ("Data-Parallel
 Layout" remarks that parameter gradients are einsums that reduce out batch).
 
 `store` is applied to exactly those tensors the device path keeps in bfloat16 between
@@ -23,7 +23,7 @@ bias, layer norm or dropout; the residual is added after the Allreduce.
 import numpy as np
 
 from .bf16 import round_to_bf16
-from .einsum import NT, einsum
+from .einsum import NT, add_broadcast, einsum, reduce
 
 B, L, M, D, F, H, K, V = ("batch", "length", "memory_length", "d_model", "d_ff",
                           "heads", "d_k", "d_v")
@@ -61,6 +61,24 @@ def ffn_bwd(x, a, w_in, w_out, dy, store=round_to_bf16):
     dw_in = einsum([x, dh], (D, F))
     dx = einsum([dh, w_in], (B, L, D))
     return dict(dw_in=dw_in, dw_out=dw_out, dx=dx, dh=dh)
+
+
+def ffn_bias_fwd(x, w_in, bias, w_out, store=round_to_bf16):
+    """The worked example as printed: y = Relu(x w + bias) v, bias[F] broadcast over the token
+    dims (section "Example: Two Fully-Connected Layers").  Returns dict(a, y)."""
+    h = add_broadcast(einsum([x, w_in], (B, L, F)), bias)
+    a = _st(NT(np.maximum(h.data, 0.0), h.dims), store)
+    y = einsum([a, w_out], (B, L, D))
+    return dict(a=a, y=y)
+
+
+def ffn_bias_bwd(x, a, w_in, w_out, dy, store=round_to_bf16):
+    """ffn_bwd plus dbias: the bias was broadcast over batch and length, so its gradient is the
+    reduce_sum of dh over those dims (a reduction that reduces out `batch`, hence an Allreduce
+    in the data-parallel layout like the other parameter gradients)."""
+    g = ffn_bwd(x, a, w_in, w_out, dy, store)
+    g["dbias"] = reduce(g["dh"], (F,), "sum")
+    return g
 
 
 # ----------------------------------------------------------------------------- attention

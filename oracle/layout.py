@@ -22,7 +22,7 @@ A mesh is a list of (name, size); a layout is a list of (tensor_dim, mesh_dim).
 import itertools
 import numpy as np
 
-from .einsum import NT, einsum, union_dims, EinsumError
+from .einsum import NT, add_broadcast, einsum, reduce, union_dims, EinsumError
 
 
 class LayoutError(ValueError):
@@ -180,3 +180,30 @@ def lowered_einsum(inputs, out_dims, mesh, layout):
                 acc = acc + local[c2].data
         reduced[c] = NT(acc, tuple(out_dims))
     return local, reduced
+
+
+def lowered_reduce(t, out_dims, op, mesh, layout):
+    """A reduction the way the mesh would run it ("Operation Implementation", paragraph
+    "Reduction"): local reduction of each slice, then an Allreduce (with the same operator)
+    over the mesh dims that reduced-out split dims map to.  Returns (local, reduced) like
+    lowered_einsum."""
+    plan = einsum_plan([t.dims], [t.data.shape], out_dims, mesh, layout)
+    combine = np.add if op == "sum" else np.maximum
+    local = {c: reduce(slice_tensor(t, mesh, layout, c), out_dims, op) for c in all_coords(mesh)}
+    reduced = {}
+    axes = plan["reduce_axes"]
+    for c in all_coords(mesh):
+        acc = None
+        for c2 in all_coords(mesh):            # processors that differ from c only along `axes`
+            if all(c2[i] == c[i] for i in range(len(mesh)) if i not in axes):
+                acc = local[c2].data if acc is None else combine(acc, local[c2].data)
+        reduced[c] = NT(acc, tuple(out_dims))
+    return local, reduced
+
+
+def lowered_add_broadcast(a, b, mesh, layout):
+    """Component-wise addition with implicit broadcasting, per processor: the layouts of the
+    operands and of the result are restrictions of one computation layout, so each processor
+    adds its slices and holds its slice of the result; no communication."""
+    return {c: add_broadcast(slice_tensor(a, mesh, layout, c), slice_tensor(b, mesh, layout, c))
+            for c in all_coords(mesh)}
