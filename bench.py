@@ -5,7 +5,7 @@ One step = one pass of the whole hot path over one batch of synthetic input: for
 backward of a full Transformer-layer shard (attention + feed-forward sublayers with their
 residual adds), every contraction in the library's HIP kernels.  Prints ONE JSON line.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload layer|ffn|mha]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload layer|ffn|ffn_bias|mha]
 
 `--workload copy` is not a benchmark of the path: it launches the library's plain copy kernel
 (fp32 -> fp32 cast) on a buffer of known size, which is what the HBM counters of a profiler run
@@ -40,7 +40,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="layer", choices=["layer", "ffn", "mha", "copy"])
+    ap.add_argument("--workload", default="layer", choices=["layer", "ffn", "ffn_bias", "mha", "copy"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -83,18 +83,27 @@ def main():
         def step():
             step_fwd()
             step_bwd()
-    elif args.workload == "ffn":
+    elif args.workload in ("ffn", "ffn_bias"):
         cfg = mtf_inputs.config2()
         B, L, D = cfg["x"].shape
         F = cfg["w_in"].shape[1]
         fwd = flops_ffn(B * L, D, F)
-        name = f"config 2: FFN shard fwd+bwd, x[{B},{L},{D}] d_ff_local={F}"
         g = {k: v.to(dev) for k, v in cfg.items()}
-        ws = torch.empty(B * L * F * 2 + 256, dtype=torch.uint8, device=dev)
+        ws = torch.empty(B * L * F * 2 + (8 << 20), dtype=torch.uint8, device=dev)
+        if args.workload == "ffn":
+            name = f"config 2: FFN shard fwd+bwd, x[{B},{L},{D}] d_ff_local={F}"
 
-        def step():
-            a, _ = mtf.ffn_fwd(g["x"], g["w_in"], g["w_out"])
-            mtf.ffn_bwd(g["x"], a, g["w_in"], g["w_out"], g["dy"], workspace=ws)
+            def step():
+                a, _ = mtf.ffn_fwd(g["x"], g["w_in"], g["w_out"])
+                mtf.ffn_bwd(g["x"], a, g["w_in"], g["w_out"], g["dy"], workspace=ws)
+        else:       # the worked example as printed: y = Relu(x w + bias) v, and dbias in backward
+            name = f"config 2 + bias: y = Relu(x w + bias) v fwd+bwd, x[{B},{L},{D}] d_ff_local={F}"
+            bias = mtf_inputs.normal(2, 9, (F,), std=0.5).to(dev)
+            cfg = dict(cfg, bias=bias.cpu())
+
+            def step():
+                a, _ = mtf.ffn_bias_fwd(g["x"], g["w_in"], bias, g["w_out"])
+                mtf.ffn_bias_bwd(g["x"], a, g["w_in"], g["w_out"], g["dy"], workspace=ws)
     else:
         cfg = mtf_inputs.config3()
         B, L, D = cfg["x"].shape
@@ -243,11 +252,15 @@ def cpu_baseline(workload, cfg):
     nb = 2                                           # batch elements in the sample
     x = NT(f64(cfg["x"][:nb]), (B, L, D))
     t0 = time.perf_counter()
-    if workload == "ffn":
+    if workload in ("ffn", "ffn_bias"):
         w_in, w_out = NT(f64(cfg["w_in"]), (D, F)), NT(f64(cfg["w_out"]), (F, D))
         dy = NT(f64(cfg["dy"][:nb]), (B, L, D))
-        f = OL.ffn_fwd(x, w_in, w_out)
-        OL.ffn_bwd(x, f["a"], w_in, w_out, dy)
+        if workload == "ffn":
+            f = OL.ffn_fwd(x, w_in, w_out)
+            OL.ffn_bwd(x, f["a"], w_in, w_out, dy)
+        else:
+            f = OL.ffn_bias_fwd(x, w_in, NT(f64(cfg["bias"]), (F,)), w_out)
+            OL.ffn_bias_bwd(x, f["a"], w_in, w_out, dy)
         T = nb * cfg["x"].shape[1]
         flops = 3 * flops_ffn(T, cfg["x"].shape[2], cfg["w_in"].shape[1])
     else:

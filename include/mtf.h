@@ -71,8 +71,16 @@ typedef enum { MTF_F32 = 0, MTF_BF16 = 1 } mtf_dtype;
 typedef enum {
   MTF_EPI_NONE = 0,
   MTF_EPI_RELU = 1,     /* out = max(value, 0) */
-  MTF_EPI_MASK_GT0 = 2  /* out = aux > 0 ? value : 0; aux has out's shape and the input dtype */
+  MTF_EPI_MASK_GT0 = 2, /* out = aux > 0 ? value : 0; aux has out's shape and the input dtype */
+  /* The worked example's hidden layer, h = Relu(einsum(x, w) + bias): aux is a tensor over the
+   * output's innermost dim (input dtype), implicitly broadcast over the other dims (section
+   * "Mesh-TensorFlow syntax": binary component-wise operations broadcast an operand whose
+   * shape is a subset of the other's). */
+  MTF_EPI_BIAS = 3,      /* out = value + aux[innermost index] */
+  MTF_EPI_BIAS_RELU = 4  /* out = max(value + aux[innermost index], 0) */
 } mtf_epilogue;
+
+typedef enum { MTF_REDUCE_SUM = 0, MTF_REDUCE_MAX = 1 } mtf_reduce_op;
 
 typedef enum {
   MTF_OK = 0,
@@ -152,6 +160,30 @@ int mtf_reduce_partials(const void* const* partials, int32_t n, const void* resi
                         mtf_dtype residual_dt, void* out, mtf_dtype out_dt, int64_t count,
                         void* stream);
 
+/* ---------------------------------------------------------------- device: component-wise addition
+ * Section "Mesh-TensorFlow syntax": out = a + b where b's dims are a subset of a's (any order);
+ * b is repeated along the dims it lacks.  out has a's shape.  Section "Operation
+ * Implementation", component-wise paragraph: each processor applies this to its slices (LOCAL
+ * shapes; the slices of a, b and out follow from one computation layout), no communication.
+ * a, b are in_dt, out is out_dt; the sum is taken in fp32.
+ * Errors: NULL, RANK, DUP_DIM, SIZE_MISMATCH, OUT_NOT_SUBSET (b has a dim a lacks), ALIGN, HIP. */
+int mtf_add_broadcast(const void* a, const mtf_shape* a_local, const void* b,
+                      const mtf_shape* b_local, void* out, mtf_dtype in_dt, mtf_dtype out_dt,
+                      void* stream);
+
+/* ---------------------------------------------------------------- device: local reduction
+ * Section "Operation Implementation", paragraph "Reduction": the output dims are a subset of
+ * the input dims (any order); every other dim is summed or maximised out.  This is the LOCAL
+ * reduction of one slice; mtf_einsum_plan(in, NULL, out, ...) gives the local shapes and the mesh
+ * dims the result must still be combined over (sum: mtf_reduce_partials).
+ * Accumulation is fp32, in a fixed order (results are reproducible run to run).
+ * workspace: device scratch of mtf_reduce_local_workspace_bytes() (may be 0 bytes / NULL then).
+ * Errors: NULL, RANK, DUP_DIM, SIZE_MISMATCH, OUT_NOT_SUBSET, ALIGN, WORKSPACE, UNSUPPORTED, HIP. */
+size_t mtf_reduce_local_workspace_bytes(const mtf_shape* in_local, const mtf_shape* out_local);
+int mtf_reduce_local(const void* in, const mtf_shape* in_local, void* out,
+                     const mtf_shape* out_local, mtf_dtype in_dt, mtf_dtype out_dt,
+                     mtf_reduce_op op, void* workspace, size_t workspace_bytes, void* stream);
+
 /* Element-wise dtype conversion (fp32 <-> bf16 round-to-nearest-even, or copy). */
 int mtf_cast(const void* in, mtf_dtype in_dt, void* out, mtf_dtype out_dt, int64_t count,
              void* stream);
@@ -181,12 +213,24 @@ typedef struct {
 int mtf_ffn_fwd(const mtf_ffn_dims* d, const void* x, const void* w_in, const void* w_out,
                 void* a, void* y_partial, void* stream);
 
+/* The worked example as printed, y = Relu(x w + bias) v (section "Example: Two Fully-Connected
+ * Layers"): as mtf_ffn_fwd with bias[d_ff] (bf16, in) added before the ReLU. */
+int mtf_ffn_bias_fwd(const mtf_ffn_dims* d, const void* x, const void* w_in, const void* bias,
+                     const void* w_out, void* a, void* y_partial, void* stream);
+
 size_t mtf_ffn_bwd_workspace_bytes(const mtf_ffn_dims* d);
 /* dy[batch,length,d_model] bf16 in;  dw_in[d_model,d_ff], dw_out[d_ff,d_model],
  * dx_partial[batch,length,d_model] fp32 out.  The ReLU mask is a > 0. */
 int mtf_ffn_bwd(const mtf_ffn_dims* d, const void* x, const void* a, const void* w_in,
                 const void* w_out, const void* dy, void* dw_in, void* dw_out, void* dx_partial,
                 void* workspace, size_t workspace_bytes, void* stream);
+
+/* As mtf_ffn_bwd, plus dbias[d_ff] (fp32, out) = reduce_sum of dh over batch and length: like
+ * the other parameter gradients it reduces out `batch` ("Data-Parallel Layout"). */
+size_t mtf_ffn_bias_bwd_workspace_bytes(const mtf_ffn_dims* d);
+int mtf_ffn_bias_bwd(const mtf_ffn_dims* d, const void* x, const void* a, const void* w_in,
+                     const void* w_out, const void* dy, void* dw_in, void* dbias, void* dw_out,
+                     void* dx_partial, void* workspace, size_t workspace_bytes, void* stream);
 
 /* Self-attention over x (memory = x).  logits = scale * q.k over d_k; softmax over the memory
  * positions; causal != 0 hides memory positions m > l.  Outputs q,k,v,ctx [batch,length,heads,

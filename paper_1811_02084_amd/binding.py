@@ -13,7 +13,8 @@ lib = C.CDLL(LIB_PATH)
 
 MAX_RANK = 8
 F32, BF16 = 0, 1
-EPI_NONE, EPI_RELU, EPI_MASK_GT0 = 0, 1, 2
+EPI_NONE, EPI_RELU, EPI_MASK_GT0, EPI_BIAS, EPI_BIAS_RELU = 0, 1, 2, 3, 4
+REDUCE_SUM, REDUCE_MAX = 0, 1
 
 STATUS = {0: "MTF_OK", -1: "MTF_ERR_NULL", -2: "MTF_ERR_DUP_DIM", -3: "MTF_ERR_SIZE_MISMATCH",
           -4: "MTF_ERR_INDIVISIBLE", -5: "MTF_ERR_LAYOUT_CONFLICT", -6: "MTF_ERR_DUP_RULE",
@@ -72,8 +73,9 @@ class MtfError(RuntimeError):
 
 lib.mtf_status_string.restype = C.c_char_p
 lib.mtf_last_error.restype = C.c_char_p
-for _f in ("mtf_ffn_bwd_workspace_bytes", "mtf_mha_bwd_workspace_bytes",
-           "mtf_layer_fwd_workspace_bytes", "mtf_layer_bwd_workspace_bytes"):
+for _f in ("mtf_ffn_bwd_workspace_bytes", "mtf_ffn_bias_bwd_workspace_bytes", "mtf_mha_bwd_workspace_bytes",
+           "mtf_layer_fwd_workspace_bytes", "mtf_layer_bwd_workspace_bytes",
+           "mtf_reduce_local_workspace_bytes"):
     if hasattr(lib, _f):
         getattr(lib, _f).restype = C.c_size_t
 
@@ -255,6 +257,34 @@ def reduce_partials(partials, residual=None, out_dtype=torch.float32, out=None):
     return out
 
 
+def add_broadcast(a, a_dims, b, b_dims, out_dtype=None):
+    """a + b with b's dims a subset of a's (b repeated along the dims it lacks)."""
+    k = _Keep()
+    sa = k.shape(_named(a, a_dims))
+    sb = k.shape(_named(b, b_dims))
+    out = torch.empty(a.shape, dtype=out_dtype or a.dtype, device=a.device)
+    _check(lib.mtf_add_broadcast(_ptr(a), C.byref(sa), _ptr(b), C.byref(sb), _ptr(out), _dt(a), _dt(out),
+                                 _stream()))
+    return out
+
+
+def reduce_local(x, x_dims, out_dims, op=REDUCE_SUM, out_dtype=torch.float32):
+    """reduce_sum / reduce_max of one slice: dims of x not named in out_dims are reduced out."""
+    k = _Keep()
+    named = _named(x, x_dims)
+    sizes = dict(named)
+    sx = k.shape(named)
+    missing = [d for d in out_dims if d not in sizes]
+    out_shape = [(d, sizes.get(d, 1)) for d in out_dims]
+    out = torch.empty([1] if missing else [n for _, n in out_shape], dtype=out_dtype, device=x.device)
+    so = k.shape(out_shape)
+    need = lib.mtf_reduce_local_workspace_bytes(C.byref(sx), C.byref(so))
+    ws = _ws(need, x.device)
+    _check(lib.mtf_reduce_local(_ptr(x), C.byref(sx), _ptr(out), C.byref(so), _dt(x), _dt(out), int(op),
+                                _ptr(ws), C.c_size_t(ws.numel()), _stream()))
+    return out
+
+
 def cast(x, dtype):
     out = torch.empty(x.shape, dtype=dtype, device=x.device)
     _check(lib.mtf_cast(_ptr(x), _dt(x), _ptr(out), _dt(out), C.c_int64(x.numel()), _stream()))
@@ -288,6 +318,31 @@ def ffn_bwd(x, a, w_in, w_out, dy, workspace=None):
     _check(lib.mtf_ffn_bwd(C.byref(d), _ptr(x), _ptr(a), _ptr(w_in), _ptr(w_out), _ptr(dy), _ptr(dw_in),
                            _ptr(dw_out), _ptr(dx), _ptr(ws), C.c_size_t(ws.numel()), _stream()))
     return dict(dw_in=dw_in, dw_out=dw_out, dx=dx)
+
+
+def ffn_bias_fwd(x, w_in, bias, w_out):
+    """The worked example with its bias: a = relu(x w_in + bias), y_partial = a w_out."""
+    b, l, dm = x.shape
+    d = mtf_ffn_dims(b, l, dm, w_in.shape[1])
+    a = torch.empty((b, l, w_in.shape[1]), dtype=torch.bfloat16, device=x.device)
+    y = torch.empty((b, l, dm), dtype=torch.float32, device=x.device)
+    _check(lib.mtf_ffn_bias_fwd(C.byref(d), _ptr(x), _ptr(w_in), _ptr(bias), _ptr(w_out), _ptr(a), _ptr(y),
+                                _stream()))
+    return a, y
+
+
+def ffn_bias_bwd(x, a, w_in, w_out, dy, workspace=None):
+    b, l, dm = x.shape
+    d = mtf_ffn_dims(b, l, dm, w_in.shape[1])
+    need = lib.mtf_ffn_bias_bwd_workspace_bytes(C.byref(d))
+    ws = workspace if workspace is not None else _ws(need, x.device)
+    dw_in = torch.empty(w_in.shape, dtype=torch.float32, device=x.device)
+    dw_out = torch.empty(w_out.shape, dtype=torch.float32, device=x.device)
+    dbias = torch.empty(w_in.shape[1], dtype=torch.float32, device=x.device)
+    dx = torch.empty(x.shape, dtype=torch.float32, device=x.device)
+    _check(lib.mtf_ffn_bias_bwd(C.byref(d), _ptr(x), _ptr(a), _ptr(w_in), _ptr(w_out), _ptr(dy), _ptr(dw_in),
+                                _ptr(dbias), _ptr(dw_out), _ptr(dx), _ptr(ws), C.c_size_t(ws.numel()), _stream()))
+    return dict(dw_in=dw_in, dw_out=dw_out, dbias=dbias, dx=dx)
 
 
 def mha_fwd(x, w_q, w_k, w_v, w_o, scale, causal):

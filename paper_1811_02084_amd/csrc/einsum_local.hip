@@ -17,6 +17,7 @@ struct GenericArgs {
   int64_t out_extent[kMaxLoops], out_sa[kMaxLoops], out_sb[kMaxLoops];  // OUT's dims, row-major
   int64_t red_extent[kMaxLoops], red_sa[kMaxLoops], red_sb[kMaxLoops];  // summed-out dims
   int64_t out_elems, red_points;
+  int64_t bias_extent;  // > 0: aux is a bias over OUT's innermost dim (that many values)
   float alpha;
   int accumulate, epi, has_b;
 };
@@ -64,6 +65,7 @@ __global__ void __launch_bounds__(256) einsum_generic_kernel(const InT* __restri
     }
     float v = g.alpha * acc;
     if (g.accumulate) v += sizeof(OutT) == 2 ? bf16_to_f32((bf16_t)out[o]) : (float)out[o];
+    if (g.bias_extent > 0) v += load_in<InT>(aux, o % g.bias_extent);
     if (g.epi == MTF_EPI_RELU) v = fmaxf(v, 0.f);
     if (g.epi == MTF_EPI_MASK_GT0) v = load_in<InT>(aux, o) > 0.f ? v : 0.f;
     if (sizeof(OutT) == 2)
@@ -114,6 +116,11 @@ int launch_generic(const void* a, const Dims& da, const void* b, const Dims* db,
     if (find(dout, dbb.name[i]) < 0 && find(da, dbb.name[i]) < 0) add_red(dbb.name[i], dbb.size[i]);
   g.alpha = alpha;
   g.accumulate = accumulate;
+  g.bias_extent = 0;
+  if (epi == MTF_EPI_BIAS || epi == MTF_EPI_BIAS_RELU) {
+    g.bias_extent = dout.rank ? dout.size[dout.rank - 1] : 1;
+    epi = epi == MTF_EPI_BIAS_RELU ? MTF_EPI_RELU : MTF_EPI_NONE;
+  }
   g.epi = epi;
   g.has_b = db ? 1 : 0;
   const int blocks = (int)std::min<int64_t>(ceil_div(g.out_elems, 256), 256 * 32);
@@ -216,9 +223,10 @@ extern "C" int mtf_einsum_local(const void* a, const mtf_shape* a_local, const v
   if (!a || !out) return fail(MTF_ERR_NULL, "a / out");
   if ((in_dt != MTF_F32 && in_dt != MTF_BF16) || (out_dt != MTF_F32 && out_dt != MTF_BF16))
     return fail(MTF_ERR_UNSUPPORTED, "dtype");
-  if (epi != MTF_EPI_NONE && epi != MTF_EPI_RELU && epi != MTF_EPI_MASK_GT0)
+  const bool with_bias = epi == MTF_EPI_BIAS || epi == MTF_EPI_BIAS_RELU;
+  if (epi != MTF_EPI_NONE && epi != MTF_EPI_RELU && epi != MTF_EPI_MASK_GT0 && !with_bias)
     return fail(MTF_ERR_UNSUPPORTED, "epilogue %d", (int)epi);
-  if (epi == MTF_EPI_MASK_GT0 && !aux) return fail(MTF_ERR_NULL, "aux for MTF_EPI_MASK_GT0");
+  if ((epi == MTF_EPI_MASK_GT0 || with_bias) && !aux) return fail(MTF_ERR_NULL, "aux for this epilogue");
   if (!aligned16(a) || !aligned16(b) || !aligned16(out) || !aligned16(aux))
     return fail(MTF_ERR_ALIGN, "a / b / out / aux");
   Canon c;
@@ -232,11 +240,15 @@ extern "C" int mtf_einsum_local(const void* a, const mtf_shape* a_local, const v
       d.B[0] = static_cast<const bf16_t*>(swapped ? a : b);
       d.C = out;
       d.out_bf16 = out_dt == MTF_BF16;
-      d.epi = epi;
-      d.aux = static_cast<const bf16_t*>(aux);
+      d.epi = with_bias ? (epi == MTF_EPI_BIAS_RELU ? MTF_EPI_RELU : MTF_EPI_NONE) : epi;
+      d.aux = with_bias ? nullptr : static_cast<const bf16_t*>(aux);
+      // the bias runs over OUT's innermost dim: a plain n-vector unless that dim was merged
+      // with the one before it
+      d.bias = with_bias ? static_cast<const bf16_t*>(aux) : nullptr;
+      const bool bias_ok = !with_bias || (dout.rank > 0 && d.N == dout.size[dout.rank - 1]);
       d.alpha = alpha;
       d.accumulate = accumulate != 0;
-      if (gemm_bf16_supported(d)) return gemm_bf16_launch(d, s);
+      if (bias_ok && gemm_bf16_supported(d)) return gemm_bf16_launch(d, s);
     }
   }
   return launch_generic(a, da, has_b ? b : nullptr, has_b ? &db : nullptr, out, dout, in_dt, out_dt,

@@ -29,6 +29,9 @@ struct GemmDesc {
   bool out_bf16 = false;
   int epi = MTF_EPI_NONE;      // mtf_epilogue
   const bf16_t* aux = nullptr; // MTF_EPI_MASK_GT0: same shape / ldc / batch strides as C
+  // optional: bias[n] (N values, 8-byte aligned) added to every row after alpha / accumulate and
+  // before the epilogue: C = epi(alpha * sum + old C + bias).  Not with grouped launches.
+  const bf16_t* bias = nullptr;
   float alpha = 1.f;
   bool accumulate = false;
   // batch: z = z0 * batch1 + z1

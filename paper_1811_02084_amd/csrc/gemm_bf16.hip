@@ -70,6 +70,7 @@ struct GemmArgs {
   int64_t lda[kMaxGroup], ldb[kMaxGroup], ldc[kMaxGroup];
   void* C[kMaxGroup];
   const bf16_t* aux;
+  const bf16_t* bias;
   float alpha;
   int accumulate;
   int tiles_m[kMaxGroup], tiles_n[kMaxGroup];
@@ -382,6 +383,15 @@ __global__ void __launch_bounds__(Cfg::kThreads, Cfg::kWavesPerSimd) gemm_bf16_k
   const int lane_m = lane & 31, lane_h = lane >> 5;
   const int out_row = lane >> 4, out_col = (lane & 15) * 4;  // read-back: 4 rows per instruction
   void* const Cg = g.C[grp];
+  // a lane reads back the same 4 columns of every slab: its bias values are loaded once
+  float bias4[4] = {0.f, 0.f, 0.f, 0.f};
+  if (g.bias && n0 + wave_n + out_col < N) {
+    const uint2 b2 = *reinterpret_cast<const uint2*>(g.bias + n0 + wave_n + out_col);
+    bias4[0] = __uint_as_float(b2.x << 16);
+    bias4[1] = __uint_as_float(b2.x & 0xffff0000u);
+    bias4[2] = __uint_as_float(b2.y << 16);
+    bias4[3] = __uint_as_float(b2.y & 0xffff0000u);
+  }
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
 #pragma unroll
@@ -418,6 +428,8 @@ __global__ void __launch_bounds__(Cfg::kThreads, Cfg::kWavesPerSimd) gemm_bf16_k
           v[3] += old.w;
         }
       }
+#pragma unroll
+      for (int e = 0; e < 4; ++e) v[e] += bias4[e];
       if (EPI == MTF_EPI_RELU) {
 #pragma unroll
         for (int e = 0; e < 4; ++e) v[e] = fmaxf(v[e], 0.f);
@@ -509,6 +521,7 @@ bool gemm_bf16_supported(const GemmDesc& d) {
     if (!aligned16(d.A[s]) || !aligned16(d.B[s])) return false;
   }
   if (!aligned16(d.C) || (d.epi == MTF_EPI_MASK_GT0 && (!d.aux || !aligned16(d.aux)))) return false;
+  if (d.bias && (((uintptr_t)d.bias & 7) || d.nextra > 0)) return false;
   if (d.batch0 * d.batch1 > 65535) return false;
   if (d.nextra < 0 || d.nextra > kMaxGroup - 1) return false;
   if (d.nextra > 0 && (d.nseg != 1 || d.batch0 * d.batch1 != 1 || d.accumulate || d.epi != MTF_EPI_NONE))
@@ -547,6 +560,7 @@ int gemm_bf16_launch(const GemmDesc& d, hipStream_t stream) {
     a.lda[p + 1] = e.lda; a.ldb[p + 1] = e.ldb; a.ldc[p + 1] = e.ldc;
   }
   a.aux = d.aux;
+  a.bias = d.bias;
   a.alpha = d.alpha;
   a.accumulate = d.accumulate ? 1 : 0;
   a.batch1 = (int)d.batch1;

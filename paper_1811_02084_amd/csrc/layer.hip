@@ -5,6 +5,7 @@
 #include "attention.h"
 #include "device_common.h"
 #include "gemm_bf16.h"
+#include "reduce_local.h"
 
 namespace mtf {
 namespace {
@@ -118,19 +119,23 @@ MhaBwdScratch mha_bwd_scratch(const mtf_mha_dims* d, void* base) {
 }
 
 // Returns the number of buffers of `y` written (their sum is y_partial), or a negative error.
-int ffn_fwd(const mtf_ffn_dims* d, const void* x, const void* w_in, const void* w_out, void* a,
-            const Partials& y, hipStream_t s) {
+// `bias` (or nullptr): bias[F] added before the ReLU.
+int ffn_fwd(const mtf_ffn_dims* d, const void* x, const void* w_in, const void* bias, const void* w_out,
+            void* a, const Partials& y, hipStream_t s) {
   const int64_t T = d->batch * d->length, D = d->d_model, F = d->d_ff;
-  // a = relu(einsum(x[b,l,D], w_in[D,F] -> [b,l,F]))
+  // a = relu(einsum(x[b,l,D], w_in[D,F] -> [b,l,F]) [+ bias[F]])
   GemmDesc g1 = gemm(x, true, w_in, false, a, true, T, F, D);
   g1.epi = MTF_EPI_RELU;
+  g1.bias = static_cast<const bf16_t*>(bias);
   if (int rc = gemm_bf16_launch(g1, s)) return rc;
   // y_partial = einsum(a[b,l,F], w_out[F,D] -> [b,l,D]); F is the split, reduced-out dim
   return gemm_k_split(a, true, w_out, false, y, T, D, F, s);
 }
 
+// `dbias` (or nullptr): dbias[F] = sum of dh over the tokens, using `red_ws`.
 int ffn_bwd(const mtf_ffn_dims* d, const void* x, const void* a, const void* w_in, const void* w_out,
-            const void* dy, void* dw_in, void* dw_out, const Partials& dx, void* dh, hipStream_t s) {
+            const void* dy, void* dw_in, void* dw_out, const Partials& dx, void* dh, hipStream_t s,
+            void* dbias = nullptr, void* red_ws = nullptr, size_t red_ws_bytes = 0) {
   const int64_t T = d->batch * d->length, D = d->d_model, F = d->d_ff;
   // dw_out = einsum(a[b,l,F], dy[b,l,D] -> [F,D])
   if (int rc = gemm_bf16_launch(gemm(a, false, dy, false, dw_out, false, F, D, T), s)) return rc;
@@ -139,6 +144,11 @@ int ffn_bwd(const mtf_ffn_dims* d, const void* x, const void* a, const void* w_i
   g.epi = MTF_EPI_MASK_GT0;
   g.aux = static_cast<const bf16_t*>(a);
   if (int rc = gemm_bf16_launch(g, s)) return rc;
+  // dbias = reduce_sum(dh[b,l,F] -> [F])
+  if (dbias)
+    if (int rc = reduce_cols_sum(static_cast<const bf16_t*>(dh), static_cast<float*>(dbias), T, F, red_ws,
+                                 red_ws_bytes, s))
+      return rc;
   // dw_in = einsum(x[b,l,D], dh[b,l,F] -> [D,F])
   if (int rc = gemm_bf16_launch(gemm(x, false, dh, false, dw_in, false, D, F, T), s)) return rc;
   // dx_partial = einsum(dh[b,l,F], w_in[D,F] -> [b,l,D])
@@ -231,7 +241,7 @@ int mtf_ffn_fwd(const mtf_ffn_dims* d, const void* x, const void* w_in, const vo
                 void* y_partial, void* stream) {
   if (int rc = check_ffn(d)) return rc;
   if (int rc = check_ptrs({x, w_in, w_out, a, y_partial}, "mtf_ffn_fwd buffer")) return rc;
-  const int rc = ffn_fwd(d, x, w_in, w_out, a, single(y_partial), static_cast<hipStream_t>(stream));
+  const int rc = ffn_fwd(d, x, w_in, nullptr, w_out, a, single(y_partial), static_cast<hipStream_t>(stream));
   return rc < 0 ? rc : MTF_OK;
 }
 
@@ -249,6 +259,34 @@ int mtf_ffn_bwd(const mtf_ffn_dims* d, const void* x, const void* a, const void*
     return fail(MTF_ERR_WORKSPACE, "mtf_ffn_bwd needs %zu bytes", mtf_ffn_bwd_workspace_bytes(d));
   const int rc = ffn_bwd(d, x, a, w_in, w_out, dy, dw_in, dw_out, single(dx_partial), workspace,
                          static_cast<hipStream_t>(stream));
+  return rc < 0 ? rc : MTF_OK;
+}
+
+int mtf_ffn_bias_fwd(const mtf_ffn_dims* d, const void* x, const void* w_in, const void* bias,
+                     const void* w_out, void* a, void* y_partial, void* stream) {
+  if (int rc = check_ffn(d)) return rc;
+  if (int rc = check_ptrs({x, w_in, bias, w_out, a, y_partial}, "mtf_ffn_bias_fwd buffer")) return rc;
+  const int rc = ffn_fwd(d, x, w_in, bias, w_out, a, single(y_partial), static_cast<hipStream_t>(stream));
+  return rc < 0 ? rc : MTF_OK;
+}
+
+size_t mtf_ffn_bias_bwd_workspace_bytes(const mtf_ffn_dims* d) {
+  if (!d || d->batch <= 0 || d->length <= 0 || d->d_ff <= 0) return 0;
+  return mtf_ffn_bwd_workspace_bytes(d) + round256(reduce_cols_workspace_bytes(d->batch * d->length, d->d_ff));
+}
+
+int mtf_ffn_bias_bwd(const mtf_ffn_dims* d, const void* x, const void* a, const void* w_in,
+                     const void* w_out, const void* dy, void* dw_in, void* dbias, void* dw_out,
+                     void* dx_partial, void* workspace, size_t workspace_bytes, void* stream) {
+  if (int rc = check_ffn(d)) return rc;
+  if (int rc = check_ptrs({x, a, w_in, w_out, dy, dw_in, dbias, dw_out, dx_partial}, "mtf_ffn_bias_bwd buffer"))
+    return rc;
+  if (!workspace || workspace_bytes < mtf_ffn_bias_bwd_workspace_bytes(d) || !aligned16(workspace))
+    return fail(MTF_ERR_WORKSPACE, "mtf_ffn_bias_bwd needs %zu bytes", mtf_ffn_bias_bwd_workspace_bytes(d));
+  const size_t dh_bytes = mtf_ffn_bwd_workspace_bytes(d);
+  const int rc = ffn_bwd(d, x, a, w_in, w_out, dy, dw_in, dw_out, single(dx_partial), workspace,
+                         static_cast<hipStream_t>(stream), dbias, static_cast<char*>(workspace) + dh_bytes,
+                         workspace_bytes - dh_bytes);
   return rc < 0 ? rc : MTF_OK;
 }
 
@@ -318,7 +356,7 @@ int mtf_layer_fwd(const mtf_layer_dims* d, const void* x, const mtf_layer_weight
   if (n < 0) return n;
   if (int rc = residual_add(parts, n, x, sv->u, count, s)) return rc;
   // z = u + R(FFN(u))
-  n = ffn_fwd(&f, sv->u, w->w_in, w->w_out, sv->a, parts, s);
+  n = ffn_fwd(&f, sv->u, w->w_in, nullptr, w->w_out, sv->a, parts, s);
   if (n < 0) return n;
   return residual_add(parts, n, sv->u, z, count, s);
 }

@@ -142,3 +142,17 @@ def test_argument_validation_needs_no_gpu():
     arr = (C.c_void_p * 1)(None)
     assert lib.mtf_reduce_partials(arr, 1, None, 0, None, 0, C.c_int64(0), None) == 0        # empty: nothing to do
     assert b"MTF_ERR" in lib.mtf_last_error()
+    # the worked example with its bias, broadcasting addition, local reduction
+    assert lib.mtf_ffn_bias_fwd(C.byref(d), p, p, None, p, p, p, None) == -1                     # bias NULL
+    assert lib.mtf_ffn_bias_bwd(C.byref(d), p, p, p, p, p, p, p, p, p, None, C.c_size_t(0), None) == -11
+    assert lib.mtf_ffn_bias_bwd_workspace_bytes(C.byref(d)) >= lib.mtf_ffn_bwd_workspace_bytes(C.byref(d))
+    k = mtf.binding._Keep()
+    big, small, other = k.shape([("p", 4), ("q", 8)]), k.shape([("q", 8)]), k.shape([("z", 8)])
+    wrong = k.shape([("q", 4)])
+    assert lib.mtf_add_broadcast(p, C.byref(big), p, C.byref(other), p, 0, 0, None) == -9        # OUT_NOT_SUBSET
+    assert lib.mtf_add_broadcast(p, C.byref(big), p, C.byref(wrong), p, 0, 0, None) == -3        # SIZE_MISMATCH
+    assert lib.mtf_add_broadcast(None, C.byref(big), p, C.byref(small), p, 0, 0, None) == -1
+    assert lib.mtf_reduce_local(p, C.byref(big), p, C.byref(other), 0, 0, 0, None, C.c_size_t(0), None) == -9
+    assert lib.mtf_reduce_local(p, C.byref(big), p, C.byref(small), 0, 0, 7, None, C.c_size_t(0), None) == -10
+    assert lib.mtf_reduce_local(p, C.byref(big), p, C.byref(small), 0, 0, 0, None, C.c_size_t(0), None) == -11
+    assert lib.mtf_reduce_local_workspace_bytes(C.byref(big), C.byref(small)) > 0
