@@ -5,7 +5,7 @@ One step = one pass of the whole hot path over one batch of synthetic input: for
 backward of a full Transformer-layer shard (attention + feed-forward sublayers with their
 residual adds), every contraction in the library's HIP kernels.  Prints ONE JSON line.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload layer|ffn|ffn_bias|mha]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload layer|ffn|ffn_bias|mha|vocab]
 
 `--workload copy` is not a benchmark of the path: it launches the library's plain copy kernel
 (fp32 -> fp32 cast) on a buffer of known size, which is what the HBM counters of a profiler run
@@ -40,7 +40,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="layer", choices=["layer", "ffn", "ffn_bias", "mha", "copy"])
+    ap.add_argument("--workload", default="layer", choices=["layer", "ffn", "ffn_bias", "mha", "vocab", "copy"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -104,6 +104,28 @@ def main():
             def step():
                 a, _ = mtf.ffn_bias_fwd(g["x"], g["w_in"], bias, g["w_out"])
                 mtf.ffn_bias_bwd(g["x"], a, g["w_in"], g["w_out"], g["dy"], workspace=ws)
+    elif args.workload == "vocab":
+        # one processor's share of the vocabulary-split operations (embedding; logits + softmax
+        # cross-entropy with its three reductions; their gradients); the Allreduce group is this
+        # one stripe, so the combining steps are identities and are left out
+        cfg = mtf_inputs.config6()
+        B, L, D = cfg["x"].shape
+        VL, off = cfg["w_vocab"].shape[1], cfg["vocab_offset"]
+        fwd = 2.0 * B * L * D * VL                                  # the logits einsum; the gathers count 0
+        name = f"config 6: vocab-split ops fwd+bwd, x[{B},{L},{D}] vocab_local={VL} of {cfg['vocab_total']}"
+        g = {k: (v.to(dev) if torch.is_tensor(v) else v) for k, v in cfg.items()}
+        dims_x, dims_w, dims_z = ("batch", "length", "d_model"), ("d_model", "vocab"), ("batch", "length", "vocab")
+
+        def step():
+            mtf.embedding_local(g["ids"], g["table"], off)
+            z = mtf.einsum_local(g["x"], dims_x, g["w_vocab"], dims_w, dims_z, out_dtype=torch.float32)
+            m = mtf.reduce_local(z, dims_z, dims_z[:2], mtf.REDUCE_MAX)
+            s, t = mtf.xent_stats_local(z, m, g["targets"], off)
+            mtf.xent_loss(m, s, t)
+            dz = mtf.xent_grad_local(z, m, s, g["targets"], off, g["dloss"])
+            mtf.einsum_local(g["x"], dims_x, dz, dims_z, dims_w, out_dtype=torch.float32)
+            mtf.einsum_local(dz, dims_z, g["w_vocab"], dims_w, dims_x, out_dtype=torch.float32)
+            mtf.embedding_grad_local(g["ids"], g["de"], VL, off)
     else:
         cfg = mtf_inputs.config3()
         B, L, D = cfg["x"].shape
@@ -239,6 +261,31 @@ def measured_traffic(workload, kernel):
         return None
 
 
+def cpu_baseline_vocab(cfg, nb):
+    import numpy as np
+    from threadpoolctl import threadpool_info
+    from oracle import vocab as OV
+    from oracle.einsum import NT
+    f64 = lambda t: t.double().numpy()
+    off, vl = cfg["vocab_offset"], cfg["w_vocab"].shape[1]
+    x = NT(f64(cfg["x"][:nb]), (OV.B, OV.L, OV.D))
+    w = NT(f64(cfg["w_vocab"]), (OV.D, OV.VOCAB))
+    # the oracle works on a whole vocabulary: the stripe stands for it (ids folded into the stripe)
+    tg = (cfg["targets"][:nb].numpy() - off) % vl
+    ids = (cfg["ids"][:nb].numpy() - off) % vl
+    t0 = time.perf_counter()
+    OV.embedding_fwd(ids, NT(f64(cfg["table"]), (OV.VOCAB, OV.D)))
+    f = OV.xent_fwd(x, w, tg)
+    OV.xent_bwd(x, w, tg, f["logits"], f["m"], f["s"], NT(f64(cfg["dloss"][:nb]), (OV.B, OV.L)))
+    OV.embedding_bwd(ids, NT(f64(cfg["de"][:nb]), (OV.B, OV.L, OV.D)), vl)
+    dt = time.perf_counter() - t0
+    flops = 3 * 2.0 * nb * cfg["x"].shape[1] * cfg["x"].shape[2] * vl
+    threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    return {"value": round(flops / dt / 1e12, 4), "unit": "TFLOP/s", "cores": threads, "kind": "oracle",
+            "sample": f"first {nb} of {cfg['x'].shape[0]} batch elements, forward + backward, fp64 "
+                      f"(numpy; {dt:.1f} s)"}
+
+
 def cpu_baseline(workload, cfg):
     """The oracle as it stands, timed on a bounded sample of the same workload."""
     import numpy as np
@@ -250,6 +297,8 @@ def cpu_baseline(workload, cfg):
 
     f64 = lambda t: t.double().numpy()
     nb = 2                                           # batch elements in the sample
+    if workload == "vocab":
+        return cpu_baseline_vocab(cfg, nb)
     x = NT(f64(cfg["x"][:nb]), (B, L, D))
     t0 = time.perf_counter()
     if workload in ("ffn", "ffn_bias"):

@@ -184,6 +184,48 @@ int mtf_reduce_local(const void* in, const mtf_shape* in_local, void* out,
                      const mtf_shape* out_local, mtf_dtype in_dt, mtf_dtype out_dt,
                      mtf_reduce_op op, void* workspace, size_t workspace_bytes, void* stream);
 
+/* ---------------------------------------------------------------- device: vocabulary-split operations
+ * Section 'Model-Parallel "Transformer"': vocab is split across the mesh like d_ff and heads.
+ * The paper gives no formulas for the operations that carry vocab; they are taken as its own
+ * operations: embedding = einsum(onehot(ids)[batch,length,vocab], table[vocab,d_model]) (vocab
+ * reduced out: a partial sum), logits = einsum(x, w[d_model,vocab]) through mtf_einsum_local
+ * (vocab kept: a slice), loss = reduce_max + log reduce_sum(exp(logits - max)) - the target's
+ * logit, each reduction over the split vocab completed by an Allreduce over vocab's mesh dims
+ * (max: mtf_max_partials; sums: mtf_reduce_partials).  ids / targets are GLOBAL token ids
+ * (device, int32); this processor holds the vocab stripe [vocab_offset, vocab_offset +
+ * vocab_local) (mtf_slice of the vocab dim).  `count` / `rows` = batch * length tokens. */
+
+/* out_partial[t, :] = table_local[ids[t] - vocab_offset, :] where that row is local, 0 elsewhere
+ * (table bf16 [vocab_local, d_model]; out_partial [count, d_model] in out_dt; d_model % 8 == 0). */
+int mtf_embedding_local(const void* ids, int64_t count, const void* table_local,
+                        int64_t vocab_local, int64_t d_model, int64_t vocab_offset,
+                        void* out_partial, mtf_dtype out_dt, void* stream);
+/* dtable_local[v, :] (fp32, every row written) = sum over t with ids[t] == vocab_offset + v of
+ * de[t, :] (bf16), summed in token order. */
+int mtf_embedding_grad_local(const void* ids, int64_t count, const void* de, int64_t vocab_local,
+                             int64_t d_model, int64_t vocab_offset, void* dtable_local,
+                             void* stream);
+/* out[i] = max over the n (1..64) fp32 device buffers partials[k][i]: the Allreduce(max) of one
+ * group of a virtual mesh (reduce_max over a split dim).  partials: HOST array. */
+int mtf_max_partials(const void* const* partials, int32_t n, void* out, int64_t count,
+                     void* stream);
+/* Local statistics of the loss given the (already Allreduced) row maxima row_max[rows]:
+ * sumexp[r] = sum_v exp(logits_local[r, v] - row_max[r]); picked[r] = logits_local[r, targets[r] -
+ * vocab_offset] if the target is local, else 0.  logits_local fp32 [rows, vocab_local].  The local
+ * row maxima themselves come from mtf_reduce_local(MTF_REDUCE_MAX). */
+int mtf_xent_stats_local(const void* logits_local, int64_t rows, int64_t vocab_local,
+                         const void* row_max, const void* targets, int64_t vocab_offset,
+                         void* sumexp, void* picked, void* stream);
+/* loss[r] = row_max[r] + log(sumexp[r]) - picked[r] (all fp32, after their Allreduces). */
+int mtf_xent_loss(const void* row_max, const void* sumexp, const void* picked, void* loss,
+                  int64_t rows, void* stream);
+/* dlogits_local[r, v] (bf16) = (exp(logits_local[r, v] - row_max[r]) / sumexp[r]
+ *                               - [vocab_offset + v == targets[r]]) * dloss[r].
+ * vocab_local % 4 == 0.  dW and dx then are einsums of dlogits (mtf_einsum_local). */
+int mtf_xent_grad_local(const void* logits_local, int64_t rows, int64_t vocab_local,
+                        const void* row_max, const void* sumexp, const void* targets,
+                        int64_t vocab_offset, const void* dloss, void* dlogits_local, void* stream);
+
 /* Element-wise dtype conversion (fp32 <-> bf16 round-to-nearest-even, or copy). */
 int mtf_cast(const void* in, mtf_dtype in_dt, void* out, mtf_dtype out_dt, int64_t count,
              void* stream);

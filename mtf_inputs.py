@@ -105,3 +105,33 @@ def config5():
     d = layer_inputs(5, 8, 512, 1024, 16, 128, 8192, 512, 262144)
     d["causal"] = True
     return d
+
+
+def token_ids(cfg, index, shape, vocab):
+    """Integer token ids uniform in [0, vocab), int32."""
+    rng = np.random.Generator(np.random.Philox(key=[BASE_SEED, (cfg << 16) | index]))
+    return torch.from_numpy(rng.integers(0, vocab, size=shape).astype(np.int32)).contiguous()
+
+
+def vocab_inputs(cfg, batch, length, d_model, vocab_local, vocab_total=None, dtype=torch.bfloat16):
+    """Embedding table slice, output-layer weight slice, ids / targets (GLOBAL ids in
+    [0, vocab_total)), activations and incoming gradients of the vocabulary-split operations."""
+    vocab_total = vocab_total or vocab_local
+    return dict(
+        x=normal(cfg, 0, (batch, length, d_model), 1.0, dtype),
+        table=normal(cfg, 10, (vocab_local, d_model), 1.0, dtype),
+        w_vocab=normal(cfg, 11, (d_model, vocab_local), 1.0 / math.sqrt(d_model), dtype),
+        ids=token_ids(cfg, 12, (batch, length), vocab_total),
+        targets=token_ids(cfg, 13, (batch, length), vocab_total),
+        de=normal(cfg, 14, (batch, length, d_model), 1.0, dtype),
+        dloss=normal(cfg, 15, (batch, length), 1.0, torch.float32),
+        vocab_total=vocab_total,
+    )
+
+
+def config6():
+    """One processor's share of the vocabulary-split operations: 32768 tokens split 16 ways
+    (this processor holds ids 2048 .. 4095), 16 x 256 tokens, d_model 1024."""
+    d = vocab_inputs(6, 16, 256, 1024, 2048, 32768)
+    d["vocab_offset"] = 2048
+    return d

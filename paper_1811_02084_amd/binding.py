@@ -285,6 +285,60 @@ def reduce_local(x, x_dims, out_dims, op=REDUCE_SUM, out_dtype=torch.float32):
     return out
 
 
+# ------------------------------------------------------------------ vocabulary-split operations
+def embedding_local(ids, table_local, vocab_offset, out_dtype=torch.float32):
+    """ids int32 [...]; table_local bf16 [vocab_local, d_model] -> partial sum [..., d_model]."""
+    out = torch.empty(tuple(ids.shape) + (table_local.shape[1],), dtype=out_dtype, device=table_local.device)
+    _check(lib.mtf_embedding_local(_ptr(ids), C.c_int64(ids.numel()), _ptr(table_local),
+                                   C.c_int64(table_local.shape[0]), C.c_int64(table_local.shape[1]),
+                                   C.c_int64(vocab_offset), _ptr(out), _dt(out), _stream()))
+    return out
+
+
+def embedding_grad_local(ids, de, vocab_local, vocab_offset):
+    dt = torch.empty((vocab_local, de.shape[-1]), dtype=torch.float32, device=de.device)
+    _check(lib.mtf_embedding_grad_local(_ptr(ids), C.c_int64(ids.numel()), _ptr(de), C.c_int64(vocab_local),
+                                        C.c_int64(de.shape[-1]), C.c_int64(vocab_offset), _ptr(dt), _stream()))
+    return dt
+
+
+def max_partials(partials, out=None):
+    n, count = len(partials), partials[0].numel()
+    for p in partials:
+        if p.dtype != torch.float32 or p.numel() != count or not p.is_contiguous():
+            raise ValueError("partials must be contiguous fp32 tensors of one size")
+    arr = (C.c_void_p * n)(*[p.data_ptr() for p in partials])
+    if out is None:
+        out = torch.empty(partials[0].shape, dtype=torch.float32, device=partials[0].device)
+    _check(lib.mtf_max_partials(arr, n, _ptr(out), C.c_int64(count), _stream()))
+    return out
+
+
+def xent_stats_local(logits_local, row_max, targets, vocab_offset):
+    """logits_local fp32 [..., vocab_local] -> (sumexp, picked), fp32 [...]."""
+    rows, vl = logits_local.numel() // logits_local.shape[-1], logits_local.shape[-1]
+    sumexp = torch.empty(logits_local.shape[:-1], dtype=torch.float32, device=logits_local.device)
+    picked = torch.empty_like(sumexp)
+    _check(lib.mtf_xent_stats_local(_ptr(logits_local), C.c_int64(rows), C.c_int64(vl), _ptr(row_max),
+                                    _ptr(targets), C.c_int64(vocab_offset), _ptr(sumexp), _ptr(picked), _stream()))
+    return sumexp, picked
+
+
+def xent_loss(row_max, sumexp, picked):
+    loss = torch.empty_like(row_max)
+    _check(lib.mtf_xent_loss(_ptr(row_max), _ptr(sumexp), _ptr(picked), _ptr(loss), C.c_int64(row_max.numel()),
+                             _stream()))
+    return loss
+
+
+def xent_grad_local(logits_local, row_max, sumexp, targets, vocab_offset, dloss):
+    rows, vl = logits_local.numel() // logits_local.shape[-1], logits_local.shape[-1]
+    dz = torch.empty(logits_local.shape, dtype=torch.bfloat16, device=logits_local.device)
+    _check(lib.mtf_xent_grad_local(_ptr(logits_local), C.c_int64(rows), C.c_int64(vl), _ptr(row_max), _ptr(sumexp),
+                                   _ptr(targets), C.c_int64(vocab_offset), _ptr(dloss), _ptr(dz), _stream()))
+    return dz
+
+
 def cast(x, dtype):
     out = torch.empty(x.shape, dtype=dtype, device=x.device)
     _check(lib.mtf_cast(_ptr(x), _dt(x), _ptr(out), _dt(out), C.c_int64(x.numel()), _stream()))

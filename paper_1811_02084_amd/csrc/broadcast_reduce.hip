@@ -133,7 +133,15 @@ __global__ void __launch_bounds__(256) reduce_rows_kernel(const InT* __restrict_
   const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= rows) return;
   float acc = identity<OP>();
-  for (int64_t c = lane; c < cols; c += 64) acc = combine<OP>(acc, ld<InT>(in, row * cols + c));
+  if (sizeof(InT) == 4 && cols % 4 == 0) {  // fp32 rows, 16-byte aligned: 16 bytes per lane
+    const float* p = reinterpret_cast<const float*>(in) + row * cols;
+    for (int64_t c = lane * 4; c < cols; c += 256) {
+      const float4 q = *reinterpret_cast<const float4*>(p + c);
+      acc = combine<OP>(acc, combine<OP>(combine<OP>(q.x, q.y), combine<OP>(q.z, q.w)));
+    }
+  } else {
+    for (int64_t c = lane; c < cols; c += 64) acc = combine<OP>(acc, ld<InT>(in, row * cols + c));
+  }
 #pragma unroll
   for (int m = 32; m >= 1; m >>= 1) acc = combine<OP>(acc, __shfl_xor(acc, m));
   if (lane == 0) st<OutT>(out, row, acc);

@@ -156,3 +156,13 @@ def test_argument_validation_needs_no_gpu():
     assert lib.mtf_reduce_local(p, C.byref(big), p, C.byref(small), 0, 0, 7, None, C.c_size_t(0), None) == -10
     assert lib.mtf_reduce_local(p, C.byref(big), p, C.byref(small), 0, 0, 0, None, C.c_size_t(0), None) == -11
     assert lib.mtf_reduce_local_workspace_bytes(C.byref(big), C.byref(small)) > 0
+    # vocabulary-split operations
+    i64 = C.c_int64
+    assert lib.mtf_embedding_local(None, i64(4), p, i64(8), i64(16), i64(0), p, 0, None) == -1
+    assert lib.mtf_embedding_local(p, i64(4), p, i64(8), i64(12), i64(0), p, 0, None) == -10          # d_model % 8
+    assert lib.mtf_embedding_local(p, i64(0), None, i64(8), i64(16), i64(0), None, 0, None) == 0      # no tokens
+    assert lib.mtf_embedding_grad_local(p, i64(4), p, i64(0), i64(16), i64(0), p, None) == -3
+    assert lib.mtf_max_partials(None, 1, p, i64(4), None) == -1
+    assert lib.mtf_xent_stats_local(p, i64(4), i64(8), None, p, i64(0), p, p, None) == -1
+    assert lib.mtf_xent_loss(p, p, None, p, i64(4), None) == -1
+    assert lib.mtf_xent_grad_local(p, i64(4), i64(6), p, p, p, i64(0), p, p, None) == -10             # vocab % 4
