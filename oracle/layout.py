@@ -207,3 +207,68 @@ def lowered_add_broadcast(a, b, mesh, layout):
     adds its slices and holds its slice of the result; no communication."""
     return {c: add_broadcast(slice_tensor(a, mesh, layout, c), slice_tensor(b, mesh, layout, c))
             for c in all_coords(mesh)}
+
+
+# ----------------------------------------------------------------------------- reshape
+
+def reshape_plan(in_dims, out_dims, sizes, mesh, layout):
+    """Communication of a reshape that keeps the dim sizes and changes (some of) the names
+    (subsection "Reshape").  Returns one entry per mesh axis:
+      'none'       the axis splits the same position before and after (or neither);
+      'slice'      a dim is split in the output but not in the input: slicing only;
+      'allgather'  a dim is split in the input but not in the output;
+      'alltoall'   different positions are split across this mesh axis before and after."""
+    if len(in_dims) != len(out_dims) or len(in_dims) != len(sizes):
+        raise LayoutError("SIZE_MISMATCH", "reshape must keep rank and sizes")
+    lin, lout = tensor_layout(in_dims, mesh, layout), tensor_layout(out_dims, mesh, layout)
+    origin = (0,) * len(mesh)
+    slice_spec(in_dims, sizes, mesh, layout, origin)       # divisibility of both views
+    slice_spec(out_dims, sizes, mesh, layout, origin)
+    plan = []
+    for axis in range(len(mesh)):
+        pin = [i for i, d in enumerate(in_dims) if lin.get(d) == axis]
+        pout = [i for i, d in enumerate(out_dims) if lout.get(d) == axis]
+        if not pin and not pout:
+            plan.append("none")
+        elif pin and not pout:
+            plan.append("allgather")
+        elif pout and not pin:
+            plan.append("slice")
+        else:
+            plan.append("none" if pin == pout else "alltoall")
+    return plan
+
+
+def alltoall_exchange(group_slices, pos_was_split, pos_becomes_split):
+    """MPI-alltoall among the n members of one group: member i cuts its slice into n stripes
+    along `pos_becomes_split`, sends stripe j to member j, and concatenates what it receives (in
+    member order) along `pos_was_split`.  Returns the members' new slices."""
+    n = len(group_slices)
+    cut = [np.array_split(a, n, axis=pos_becomes_split) for a in group_slices]
+    return [np.concatenate([cut[src][me] for src in range(n)], axis=pos_was_split) for me in range(n)]
+
+
+def lowered_reshape(t, out_dims, mesh, layout):
+    """The reshape the way the mesh would run it, starting from every processor's input slice.
+    Per mesh axis, among the processors that differ only along that axis: an axis that splits
+    position p in the input gathers along p (allgather: the group's slices concatenated in
+    coordinate order); an axis that splits position q in the output keeps the own stripe along q.
+    An alltoall axis does both - it delivers exactly what its gather followed by its slicing
+    delivers, while moving 1/n of the data (alltoall_exchange; see the tests).  All gathers are
+    done before all slicings, so that an axis may take over a position another axis gives up.
+    Returns dict coord -> NT with the output names."""
+    plan = reshape_plan(t.dims, out_dims, t.data.shape, mesh, layout)
+    lin, lout = tensor_layout(t.dims, mesh, layout), tensor_layout(tuple(out_dims), mesh, layout)
+    cur = {c: slice_tensor(t, mesh, layout, c).data for c in all_coords(mesh)}
+    pos_in = {axis: [i for i, d in enumerate(t.dims) if lin.get(d) == axis] for axis in range(len(mesh))}
+    pos_out = {axis: [i for i, d in enumerate(out_dims) if lout.get(d) == axis] for axis in range(len(mesh))}
+    for axis, kind in enumerate(plan):                       # gathers
+        if kind in ("allgather", "alltoall"):
+            n = mesh[axis][1]
+            cur = {c: np.concatenate([cur[c[:axis] + (j,) + c[axis + 1:]] for j in range(n)], axis=pos_in[axis][0])
+                   for c in all_coords(mesh)}
+    for axis, kind in enumerate(plan):                       # slicings
+        if kind in ("slice", "alltoall"):
+            n = mesh[axis][1]
+            cur = {c: np.array_split(cur[c], n, axis=pos_out[axis][0])[c[axis]] for c in all_coords(mesh)}
+    return {c: NT(np.array(a, order="C"), tuple(out_dims)) for c, a in cur.items()}
