@@ -5,13 +5,14 @@ One step = one pass of the whole hot path over one batch of synthetic input: for
 backward of a full Transformer-layer shard (attention + feed-forward sublayers with their
 residual adds), every contraction in the library's HIP kernels.  Prints ONE JSON line.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload layer|ffn|ffn_bias|mha|vocab]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload layer|ffn|ffn_bias|mha|vocab|reshape]
 
 `--workload copy` is not a benchmark of the path: it launches the library's plain copy kernel
 (fp32 -> fp32 cast) on a buffer of known size, which is what the HBM counters of a profiler run
 are scaled by (see roofline.traffic).
 """
 import argparse
+import gc
 import json
 import math
 import os
@@ -40,7 +41,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="layer", choices=["layer", "ffn", "ffn_bias", "mha", "vocab", "copy"])
+    ap.add_argument("--workload", default="layer", choices=["layer", "ffn", "ffn_bias", "mha", "vocab", "reshape", "copy"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -60,6 +61,8 @@ def main():
 
     if args.workload == "copy":
         return copy_calibration(args, torch, mtf, dev)
+    if args.workload == "reshape":
+        return reshape_bench(args, torch, mtf, mtf_inputs, dev)
 
     # ---------------------------------------------------------------- workload
     if args.workload == "layer":
@@ -145,11 +148,14 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    gc.collect()
+    gc.disable()                     # as timeit does: no collector pause of the host inside the timed region
     t0 = time.perf_counter()
     for _ in range(args.steps):
         step()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
+    gc.enable()
     ms_per_step = elapsed * 1e3 / args.steps
     tflops = step_flops / (ms_per_step * 1e-3) / 1e12
 
@@ -240,6 +246,50 @@ def copy_calibration(args, torch, mtf, dev):
                       "bytes_read_per_launch": COPY_ELEMS * 4, "bytes_written_per_launch": COPY_ELEMS * 4,
                       "value": round(2 * COPY_ELEMS * 4 / dt / 1e9, 1), "unit": "GB/s", "steps": args.steps,
                       "warmup": args.warmup, "copied_correctly": ok}))
+    return 0 if ok else 1
+
+
+def reshape_bench(args, torch, mtf, mtf_inputs, dev):
+    """Reshape on a virtual mesh of 8 processors: activations [16384 tokens, 4096 units] switch from
+    data-parallel (tokens split) to model-parallel (units split): the alltoall case.  A step =
+    the output slices of all 8 processors.  HBM-bound copy: GB/s against 8 TB/s."""
+    mesh, layout = [("all", 8)], [("batch", "all"), ("hidden", "all")]
+    in_shape, out_shape = [("batch", 16384), ("units", 4096)], [("examples", 16384), ("hidden", 4096)]
+    full = mtf_inputs.normal(7, 0, (16384, 4096)).to(dev)
+    slices = [mtf.slice_copy(full, ("batch", "units"), mesh, layout, (c,)) for c in range(8)]
+    plan = mtf.reshape_plan(in_shape, out_shape, mesh, layout)
+
+    outs = [torch.empty((16384, 512), dtype=full.dtype, device=dev) for _ in range(8)]
+
+    def step():
+        return [mtf.reshape_virtual(slices, in_shape, out_shape, mesh, layout, (c,), out=outs[c]) for c in range(8)]
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    gc.collect()
+    gc.disable()                     # a full collection in this process pauses the host for ~40 ms
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        outs = step()
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / args.steps
+    gc.enable()
+    ok = all(torch.equal(outs[c], full[:, c * 512:(c + 1) * 512]) for c in range(8))
+    nbytes = 2 * full.numel() * 2
+    mtf.timing_enable(True)          # kernel time alone (the step above includes 8 host calls)
+    for _ in range(args.steps):
+        step()
+    kern = [r for r in mtf.timing_collect() if r["kernel"] == "reshape_kernel"][0]
+    mtf.timing_enable(False)
+    kernel_gbs = kern["bytes"] / (kern["total_ms"] * 1e-3) / 1e9
+    print(json.dumps({"metric": "reshape on a virtual mesh (alltoall case), HBM-bound copy", "plan": plan,
+                      "value": round(nbytes / dt / 1e9, 1), "unit": "GB/s", "ms_per_step": round(dt * 1e3, 4),
+                      "bytes_per_step": nbytes, "steps": args.steps, "warmup": args.warmup,
+                      "roofline": {"bound": "hbm", "achieved": round(kernel_gbs, 1), "peak": 8000.0,
+                                   "unit": "GB/s", "frac": round(kernel_gbs / 8000.0, 4), "kernel": "reshape_kernel",
+                                   "avg_launch_us": round(kern["total_ms"] * 1e3 / kern["launches"], 2)},
+                      "bit_exact": ok}))
     return 0 if ok else 1
 
 

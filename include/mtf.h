@@ -160,6 +160,29 @@ int mtf_reduce_partials(const void* const* partials, int32_t n, const void* resi
                         mtf_dtype residual_dt, void* out, mtf_dtype out_dt, int64_t count,
                         void* stream);
 
+/* ---------------------------------------------------------------- reshape (same sizes, new names)
+ * Subsection "Reshape": keeping the dim sizes and changing dim names changes the layout, and
+ * with it what each processor must hold.  `in` and `out` are GLOBAL shapes of equal rank and
+ * sizes.  Per mesh dim m, comm[m] (host array of mesh.rank entries) is the communication among
+ * the processors that differ only along m:
+ *   NONE       the same position is split over m before and after, or none is;
+ *   SLICE      a position becomes split over m: slicing on each processor, no communication;
+ *   ALLGATHER  a position was split over m and is not any more;
+ *   ALLTOALL   different positions are split over m before and after (e.g. switching between
+ *              data- and model-parallelism).
+ * Errors: those of mtf_slice for either shape; SIZE_MISMATCH if rank or sizes differ. */
+typedef enum { MTF_COMM_NONE = 0, MTF_COMM_SLICE = 1, MTF_COMM_ALLGATHER = 2, MTF_COMM_ALLTOALL = 3 } mtf_comm;
+int mtf_reshape_plan(const mtf_shape* in, const mtf_shape* out, const mtf_place* p, int32_t* comm);
+
+/* The reshape on a virtual mesh held on one GPU: writes the output slice of the processor at
+ * p->coord, gathering from the input slices of all processors - what the collectives of
+ * mtf_reshape_plan deliver to it.  in_slices: HOST array of (product of mesh sizes, at most 64)
+ * DEVICE pointers, indexed by processor rank (mtf_coord_to_rank), each that processor's slice of
+ * `in` (contiguous, mtf_slice's sizes).  Where several processors hold a copy of an element,
+ * the one with this processor's coordinates on the uninvolved mesh dims is read.  Bit-exact. */
+int mtf_reshape_virtual(const void* const* in_slices, const mtf_shape* in, const mtf_shape* out,
+                        const mtf_place* p, void* out_slice, mtf_dtype dt, void* stream);
+
 /* ---------------------------------------------------------------- device: component-wise addition
  * Section "Mesh-TensorFlow syntax": out = a + b where b's dims are a subset of a's (any order);
  * b is repeated along the dims it lacks.  out has a's shape.  Section "Operation

@@ -206,6 +206,37 @@ def einsum_plan(a, b, out, mesh, layout):
                 flops_local=fl.value)
 
 
+COMM = {0: "none", 1: "slice", 2: "allgather", 3: "alltoall"}
+
+
+def reshape_plan(in_shape, out_shape, mesh, layout):
+    """in_shape / out_shape: global shapes [(name, size)...] of equal sizes.  Returns, per mesh dim,
+    'none' | 'slice' | 'allgather' | 'alltoall'."""
+    k = _Keep()
+    si, so = k.shape(in_shape), k.shape(out_shape)
+    p = k.place(mesh, layout, None)
+    comm = (C.c_int32 * max(len(mesh), 1))()
+    _check(lib.mtf_reshape_plan(C.byref(si), C.byref(so), C.byref(p), comm))
+    return [COMM[comm[i]] for i in range(len(mesh))]
+
+
+def reshape_virtual(in_slices, in_shape, out_shape, mesh, layout, coord, out=None):
+    """in_slices: every processor's slice of the input (by rank); returns the output slice of the
+    processor at `coord` (written into `out` if given)."""
+    k = _Keep()
+    si, so = k.shape(in_shape), k.shape(out_shape)
+    p = k.place(mesh, layout, coord)
+    if out is None:
+        _, sz = slice(out_shape, mesh, layout, coord)
+        out = torch.empty(sz, dtype=in_slices[0].dtype, device=in_slices[0].device)
+    arr = (C.c_void_p * len(in_slices))(*[t.data_ptr() for t in in_slices])
+    for t in in_slices:
+        if not t.is_cuda or not t.is_contiguous():
+            raise ValueError("slices must be contiguous device tensors")
+    _check(lib.mtf_reshape_virtual(arr, C.byref(si), C.byref(so), C.byref(p), _ptr(out), _dt(out), _stream()))
+    return out
+
+
 # ------------------------------------------------------------------ device calls
 def slice_copy(full, dims, mesh, layout, coord, slice_buf=None, scatter=False):
     """Gathers the slice of `full` (scatter=False) or writes slice_buf back into it."""

@@ -123,6 +123,30 @@ int slice_of(const Dims& t, const mtf_place* p, int64_t* offset, int64_t* size) 
   return stripes(t, pl, axis, offset, size);
 }
 
+int reshape_info(const Dims& in, const Dims& out, const mtf_place* p, bool need_coord, ReshapeInfo* r) {
+  if (in.rank != out.rank) return fail(MTF_ERR_SIZE_MISMATCH, "reshape changes the rank (%d -> %d)", in.rank, out.rank);
+  for (int i = 0; i < in.rank; ++i)
+    if (in.size[i] != out.size[i])
+      return fail(MTF_ERR_SIZE_MISMATCH, "reshape changes the size of position %d (%lld -> %lld)", i,
+                  (long long)in.size[i], (long long)out.size[i]);
+  Place pl;
+  if (int rc = load_place(p, false, &pl)) return rc;
+  if (int rc = restrict_layout(in, pl, r->in_axis)) return rc;
+  if (int rc = restrict_layout(out, pl, r->out_axis)) return rc;
+  if (need_coord)
+    if (int rc = check_coord(p, &pl)) return rc;
+  int64_t in_off[MTF_MAX_RANK];
+  if (int rc = stripes(in, pl, r->in_axis, in_off, r->in_local)) return rc;
+  if (int rc = stripes(out, pl, r->out_axis, r->out_offset, r->out_local)) return rc;
+  r->rank = in.rank;
+  r->mesh_rank = pl.mesh.rank;
+  for (int m = 0; m < pl.mesh.rank; ++m) {
+    r->mesh_size[m] = pl.mesh.size[m];
+    r->coord[m] = need_coord ? p->coord[m] : 0;
+  }
+  return MTF_OK;
+}
+
 // ------------------------------------------------------------------------- canonical einsum
 static bool mergeable(const Loop& outer, const Loop& inner) {
   // outer/inner adjacent in every tensor that has them: outer stride = inner stride * extent
@@ -342,3 +366,22 @@ int mtf_einsum_plan(const mtf_shape* a, const mtf_shape* b, const mtf_shape* out
 }
 
 }  // extern "C"
+
+extern "C" int mtf_reshape_plan(const mtf_shape* in, const mtf_shape* out, const mtf_place* p, int32_t* comm) {
+  Dims din, dout;
+  if (int rc = load_shape(in, "input", &din)) return rc;
+  if (int rc = load_shape(out, "output", &dout)) return rc;
+  if (!comm) return fail(MTF_ERR_NULL, "comm");
+  ReshapeInfo r;
+  if (int rc = reshape_info(din, dout, p, false, &r)) return rc;
+  for (int m = 0; m < r.mesh_rank; ++m) {
+    int pin = -1, pout = -1;
+    for (int i = 0; i < r.rank; ++i) {
+      if (r.in_axis[i] == m) pin = i;
+      if (r.out_axis[i] == m) pout = i;
+    }
+    comm[m] = pin < 0 ? (pout < 0 ? MTF_COMM_NONE : MTF_COMM_SLICE)
+                      : (pout < 0 ? MTF_COMM_ALLGATHER : (pin == pout ? MTF_COMM_NONE : MTF_COMM_ALLTOALL));
+  }
+  return MTF_OK;
+}

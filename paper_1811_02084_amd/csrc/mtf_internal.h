@@ -31,6 +31,18 @@ inline int find(const Dims& d, const char* n) {
 // Per-dim (offset, local size) of the slice a processor holds ("Tensor Representations").
 int slice_of(const Dims& t, const mtf_place* p, int64_t* offset, int64_t* size);
 
+// A reshape that keeps rank and sizes and changes names (subsection "Reshape"): per tensor
+// position, the mesh axis that splits it before / after (-1: not split) and the local sizes.
+struct ReshapeInfo {
+  int rank, mesh_rank;
+  int64_t mesh_size[MTF_MAX_RANK];
+  int in_axis[MTF_MAX_RANK], out_axis[MTF_MAX_RANK];
+  int64_t in_local[MTF_MAX_RANK], out_local[MTF_MAX_RANK], out_offset[MTF_MAX_RANK];
+  int64_t coord[MTF_MAX_RANK];
+};
+// need_coord: also validate p->coord and fill out_offset / coord (else they are 0).
+int reshape_info(const Dims& in, const Dims& out, const mtf_place* p, bool need_coord, ReshapeInfo* r);
+
 // ---------------------------------------------------------------------------------------------
 // Canonical form of a two-operand named einsum for the device kernels.
 //

@@ -1,0 +1,138 @@
+// Reshape on a virtual mesh (subsection "Reshape"): one processor's output slice gathered from
+// the input slices of all processors held on this GPU.  A copy: HBM-bound, bit-exact.
+#include <algorithm>
+
+#include "device_common.h"
+#include "timing.h"
+
+namespace mtf {
+namespace {
+
+constexpr int kMaxProcessors = 64;
+
+struct ReshapeArgs {
+  const void* src[kMaxProcessors];  // input slice of every processor, by rank
+  int rank, mesh_rank;
+  int64_t out_local[MTF_MAX_RANK], out_offset[MTF_MAX_RANK];  // this processor's output slice
+  int64_t in_local[MTF_MAX_RANK], in_stride[MTF_MAX_RANK];     // any processor's input slice
+  int in_axis[MTF_MAX_RANK];                                   // mesh axis splitting position i in the input
+  int64_t rank_stride[MTF_MAX_RANK];                           // row-major processor numbering
+  int64_t own_rank_part;  // rank contribution of this processor's coordinates on axes the input does not use
+  int64_t runs;           // output slice elements / vec
+};
+
+// One wave per row (all positions but the innermost) at a time, its lanes over runs of VEC
+// consecutive elements of the innermost position (the host picks VEC so that a run never crosses
+// a stripe of the input or the end of a row).  The row's part of the source processor and offset
+// is computed once per row; a run adds one division by the input's stripe length.
+template <typename T, int VEC>
+__global__ void __launch_bounds__(256) reshape_kernel(ReshapeArgs g, T* __restrict__ out) {
+  const int last = g.rank - 1;
+  const int64_t rows = g.runs;  // here: number of rows
+  const uint32_t row_runs = (uint32_t)(g.out_local[last] / VEC);
+  const uint32_t in_len = (uint32_t)g.in_local[last], out_off = (uint32_t)g.out_offset[last];
+  const bool last_split = g.in_axis[last] >= 0;
+  const int64_t last_proc_stride = last_split ? g.rank_stride[g.in_axis[last]] : 0;
+  const int lane = threadIdx.x & 63;
+  for (int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6); row < rows; row += (int64_t)gridDim.x * 4) {
+    int64_t rem = row, proc = g.own_rank_part, off = 0;
+    for (int i = last - 1; i >= 0; --i) {
+      const int64_t global = g.out_offset[i] + rem % g.out_local[i];
+      rem /= g.out_local[i];
+      int64_t local = global;
+      if (g.in_axis[i] >= 0) {  // the stripe of the input that holds it, and the index inside
+        proc += (global / g.in_local[i]) * g.rank_stride[g.in_axis[i]];
+        local = global % g.in_local[i];
+      }
+      off += local * g.in_stride[i];
+    }
+    T* dst_row = out + row * (int64_t)row_runs * VEC;
+    for (uint32_t j = lane; j < row_runs; j += 64) {
+      const uint32_t global = out_off + j * VEC;
+      const uint32_t stripe = last_split ? global / in_len : 0u;
+      const uint32_t local = last_split ? global - stripe * in_len : global;
+      const T* src = static_cast<const T*>(g.src[proc + stripe * last_proc_stride]) + off + local;
+      T* dst = dst_row + j * VEC;
+      if (VEC * sizeof(T) == 16) {
+        *reinterpret_cast<uint4*>(dst) = *reinterpret_cast<const uint4*>(src);
+      } else {
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) dst[e] = src[e];
+      }
+    }
+  }
+}
+
+template <typename T>
+int launch(const ReshapeArgs& g, void* out, int vec, int64_t elems, hipStream_t s) {
+  const int blocks = (int)std::min<int64_t>(ceil_div(g.runs, 4), 256 * 32);
+  LaunchTimer timer("reshape_kernel", 0, 2.0 * elems * sizeof(T), s);
+  constexpr int kFull = 16 / sizeof(T);  // elements per 16-byte access
+  if (vec == kFull)
+    reshape_kernel<T, kFull><<<blocks, 256, 0, s>>>(g, static_cast<T*>(out));
+  else
+    reshape_kernel<T, 1><<<blocks, 256, 0, s>>>(g, static_cast<T*>(out));
+  return launch_status("reshape_kernel");
+}
+
+}  // namespace
+}  // namespace mtf
+
+using namespace mtf;
+
+extern "C" int mtf_reshape_virtual(const void* const* in_slices, const mtf_shape* in, const mtf_shape* out,
+                                   const mtf_place* p, void* out_slice, mtf_dtype dt, void* stream) {
+  Dims din, dout;
+  if (int rc = load_shape(in, "input", &din)) return rc;
+  if (int rc = load_shape(out, "output", &dout)) return rc;
+  if (!in_slices || !out_slice) return fail(MTF_ERR_NULL, "in_slices / out_slice");
+  if (dt != MTF_F32 && dt != MTF_BF16) return fail(MTF_ERR_UNSUPPORTED, "dtype %d", (int)dt);
+  ReshapeInfo r;
+  if (int rc = reshape_info(din, dout, p, true, &r)) return rc;
+  int64_t processors = 1;
+  for (int m = 0; m < r.mesh_rank; ++m) processors *= r.mesh_size[m];
+  if (processors > kMaxProcessors)
+    return fail(MTF_ERR_UNSUPPORTED, "virtual reshape over %lld processors (at most %d)", (long long)processors,
+                kMaxProcessors);
+  ReshapeArgs g{};
+  for (int64_t q = 0; q < processors; ++q) {
+    if (!in_slices[q]) return fail(MTF_ERR_NULL, "in_slices[%lld]", (long long)q);
+    g.src[q] = in_slices[q];
+  }
+  g.rank = r.rank;
+  g.mesh_rank = r.mesh_rank;
+  int64_t acc = 1;
+  for (int m = r.mesh_rank - 1; m >= 0; --m) {
+    g.rank_stride[m] = acc;
+    acc *= r.mesh_size[m];
+  }
+  bool used[MTF_MAX_RANK] = {};
+  int64_t elems = 1, stride = 1;
+  for (int i = r.rank - 1; i >= 0; --i) {
+    g.out_local[i] = r.out_local[i];
+    g.out_offset[i] = r.out_offset[i];
+    g.in_local[i] = r.in_local[i];
+    g.in_axis[i] = r.in_axis[i];
+    g.in_stride[i] = stride;
+    stride *= r.in_local[i];
+    elems *= r.out_local[i];
+    if (r.in_axis[i] >= 0) used[r.in_axis[i]] = true;
+  }
+  g.own_rank_part = 0;
+  for (int m = 0; m < r.mesh_rank; ++m)
+    if (!used[m]) g.own_rank_part += r.coord[m] * g.rank_stride[m];
+  if (elems == 0) return MTF_OK;
+  // 16-byte runs along the innermost position must stay inside one input stripe and one output
+  // row, and start 16-byte aligned in both slices
+  const int last = r.rank - 1;
+  const int full = dt == MTF_F32 ? 4 : 8;
+  if (r.out_local[last] >= ((int64_t)1 << 31) || r.in_local[last] >= ((int64_t)1 << 31))
+    return fail(MTF_ERR_UNSUPPORTED, "innermost position too long");
+  bool aligned = aligned16(out_slice) && r.out_local[last] % full == 0 && r.out_offset[last] % full == 0 &&
+                 r.in_local[last] % full == 0;
+  for (int64_t q = 0; q < processors; ++q) aligned = aligned && aligned16(in_slices[q]);
+  const int vec = aligned ? full : 1;
+  g.runs = elems / r.out_local[last];  // rows
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  return dt == MTF_F32 ? launch<float>(g, out_slice, vec, elems, s) : launch<bf16_t>(g, out_slice, vec, elems, s);
+}

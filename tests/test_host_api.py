@@ -166,3 +166,26 @@ def test_argument_validation_needs_no_gpu():
     assert lib.mtf_xent_stats_local(p, i64(4), i64(8), None, p, i64(0), p, p, None) == -1
     assert lib.mtf_xent_loss(p, p, None, p, i64(4), None) == -1
     assert lib.mtf_xent_grad_local(p, i64(4), i64(6), p, p, p, i64(0), p, p, None) == -10             # vocab % 4
+
+
+def test_reshape_plan_matches_oracle_and_the_papers_three_cases():
+    from oracle.layout import reshape_plan as o_plan
+    mesh, layout = [("all", 4)], [("batch", "all"), ("hidden", "all")]
+    shp = lambda dims, sizes=(8, 12): list(zip(dims, sizes))
+    assert mtf.reshape_plan(shp(("batch", "io")), shp(("rows", "io")), mesh, layout) == ["allgather"]
+    assert mtf.reshape_plan(shp(("rows", "io")), shp(("batch", "io")), mesh, layout) == ["slice"]
+    assert mtf.reshape_plan(shp(("batch", "units")), shp(("examples", "hidden")), mesh, layout) == ["alltoall"]
+    two = [("rows", 2), ("cols", 2)]
+    lay2 = [("batch", "rows"), ("hidden", "cols"), ("vocab", "cols"), ("z", "rows")]
+    names = ["batch", "hidden", "vocab", "z", "p", "q"]
+    import itertools
+    for a in itertools.permutations(names, 2):
+        for b in itertools.permutations(names, 2):
+            try:
+                want = o_plan(a, b, (8, 12), two, lay2)
+            except Exception as e:              # both must refuse, with the same code
+                with pytest.raises(mtf.MtfError) as got:
+                    mtf.reshape_plan(shp(a), shp(b), two, lay2)
+                assert got.value.name == "MTF_ERR_" + e.code, (a, b)
+                continue
+            assert mtf.reshape_plan(shp(a), shp(b), two, lay2) == want, (a, b)
