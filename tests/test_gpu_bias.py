@@ -183,3 +183,41 @@ def test_example_with_bias_on_virtual_meshes(mtf):
                 offs, locs = slice_spec(out_dims, want.data.shape, mesh, layout, c)
                 idx = tuple(slice(o, o + n) for o, n in zip(offs, locs))
                 assert np.array_equal(total.double().cpu().numpy(), want.data[idx]), (name, out_dims, c)
+
+
+def test_example_on_the_three_dimensional_layout(mtf):
+    """batch -> rows, hidden -> cols, io -> planes: every matrix is tiled across two mesh dims and
+    replicated in the third, and every einsum needs an Allreduce across one mesh dim ("Data-
+    Parallel, Model-Parallel Layouts", last layout).  The hidden layer's sum must be complete
+    before the bias and the ReLU, so these run as component-wise operations after the reduce."""
+    b, d_io, d_h = 8, 16, 32
+    x = mtf_inputs.small_ints(25, 0, (b, 1, d_io), dtype=torch.float32)
+    w = mtf_inputs.small_ints(25, 1, (d_io, d_h), dtype=torch.float32)
+    bias = mtf_inputs.small_ints(25, 2, (d_h,), dtype=torch.float32)
+    v = mtf_inputs.small_ints(25, 3, (d_h, d_io), dtype=torch.float32)
+    f64 = lambda t, dims: nt(t.double().numpy(), dims)
+    full = OL.ffn_bias_fwd(f64(x, (B, L, D)), f64(w, (D, F)), f64(bias, (F,)), f64(v, (F, D)), OL.identity)
+    mesh = [("rows", 2), ("cols", 2), ("planes", 2)]
+    layout = [("batch", "rows"), ("d_ff", "cols"), ("d_model", "planes")]
+    coords = all_coords(mesh)
+    shp = lambda dims, sizes: list(zip(dims, sizes))
+    p1 = mtf.einsum_plan(shp((B, L, D), (b, 1, d_io)), shp((D, F), (d_io, d_h)), shp((B, L, F), (b, 1, d_h)), mesh, layout)
+    p2 = mtf.einsum_plan(shp((B, L, F), (b, 1, d_h)), shp((F, D), (d_h, d_io)), shp((B, L, D), (b, 1, d_io)), mesh, layout)
+    assert p1["reduce_axes"] == [2] and p2["reduce_axes"] == [1]           # planes, then cols
+    group = lambda c, axes: [c2 for c2 in coords if all(c2[i] == c[i] for i in range(3) if i not in axes)]
+    sl = lambda t, dims, c: mtf.slice_copy(_dev(t), dims, mesh, layout, c)
+    h_part = {c: mtf.einsum_local(sl(x, (B, L, D), c), (B, L, D), sl(w, (D, F), c), (D, F), (B, L, F)) for c in coords}
+    a = {}
+    for c in coords:
+        h = mtf.reduce_partials([h_part[g] for g in group(c, [2])])
+        h = mtf.add_broadcast(h, (B, L, F), sl(bias, (F,), c), (F,))
+        a[c] = mtf.einsum_local(h, (B, L, F), None, None, (B, L, F), epi=mtf.EPI_RELU)      # component-wise
+        offs, locs = slice_spec((B, L, F), full["a"].data.shape, mesh, layout, c)
+        idx = tuple(slice(o, o + n) for o, n in zip(offs, locs))
+        assert np.array_equal(a[c].double().cpu().numpy(), full["a"].data[idx]), c
+    y_part = {c: mtf.einsum_local(a[c], (B, L, F), sl(v, (F, D), c), (F, D), (B, L, D)) for c in coords}
+    for c in coords:
+        y = mtf.reduce_partials([y_part[g] for g in group(c, [1])])
+        offs, locs = slice_spec((B, L, D), full["y"].data.shape, mesh, layout, c)
+        idx = tuple(slice(o, o + n) for o, n in zip(offs, locs))
+        assert np.array_equal(y.double().cpu().numpy(), full["y"].data[idx]), c
