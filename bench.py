@@ -5,7 +5,7 @@ One step = one pass of the whole hot path over one batch of synthetic input: for
 backward of a full Transformer-layer shard (attention + feed-forward sublayers with their
 residual adds), every contraction in the library's HIP kernels.  Prints ONE JSON line.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload layer|ffn|ffn_bias|mha|vocab|reshape]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload layer|ffn|ffn_bias|mha|attention_lm|vocab|reshape]
 
 `--workload copy` is not a benchmark of the path: it launches the library's plain copy kernel
 (fp32 -> fp32 cast) on a buffer of known size, which is what the HBM counters of a profiler run
@@ -41,7 +41,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="layer", choices=["layer", "ffn", "ffn_bias", "mha", "vocab", "reshape", "copy"])
+    ap.add_argument("--workload", default="layer", choices=["layer", "ffn", "ffn_bias", "mha", "attention_lm", "vocab", "reshape", "copy"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -107,6 +107,21 @@ def main():
             def step():
                 a, _ = mtf.ffn_bias_fwd(g["x"], g["w_in"], bias, g["w_out"])
                 mtf.ffn_bias_bwd(g["x"], a, g["w_in"], g["w_out"], g["dy"], workspace=ws)
+    elif args.workload == "attention_lm":
+        # the attention core at the head width of the paper's language models (d_k = d_v = 256):
+        # 8 local heads of width 256 (the same 2048 columns as config 5), causal, 8 x 512 tokens
+        B, L, H, K = 8, 512, 8, 256
+        causal, scale = True, 1.0 / math.sqrt(K)
+        pairs = L * (L + 1) / 2
+        fwd = 2 * 2.0 * B * H * pairs * K
+        name = f"attention core fwd+bwd, q/k/v[{B},{L},{H},{K}] causal (unfused: einsums + row softmax)"
+        cfg = {n: mtf_inputs.normal(8, i, (B, L, H, K)) for i, n in enumerate(("q", "k", "v", "dctx"))}
+        cfg.update(scale=scale, causal=causal)
+        g = {n: (t.to(dev) if torch.is_tensor(t) else t) for n, t in cfg.items()}
+
+        def step():
+            ctx, lse = mtf.attention_fwd(g["q"], g["k"], g["v"], scale, causal)
+            mtf.attention_bwd(g["q"], g["k"], g["v"], ctx, lse, g["dctx"], scale, causal)
     elif args.workload == "vocab":
         # one processor's share of the vocabulary-split operations (embedding; logits + softmax
         # cross-entropy with its three reductions; their gradients); the Allreduce group is this
@@ -349,6 +364,23 @@ def cpu_baseline(workload, cfg):
     nb = 2                                           # batch elements in the sample
     if workload == "vocab":
         return cpu_baseline_vocab(cfg, nb)
+    if workload == "attention_lm":
+        from oracle import layer as OLA
+        from oracle.einsum import NT as NTA
+        qn, kn, vn, dn = (NTA(f64(cfg[n][:nb]), dims) for n, dims in
+                          (("q", (OLA.B, OLA.L, OLA.H, OLA.K)), ("k", (OLA.B, OLA.M, OLA.H, OLA.K)),
+                           ("v", (OLA.B, OLA.M, OLA.H, OLA.V)), ("dctx", (OLA.B, OLA.L, OLA.H, OLA.V))))
+        t0 = time.perf_counter()
+        ctx, lse = OLA.attention_core_fwd(qn, kn, vn, cfg["scale"], True)
+        OLA.attention_core_bwd(qn, kn, vn, ctx, lse, dn, cfg["scale"], True)
+        dt = time.perf_counter() - t0
+        _, Lq, Hq, Kq = cfg["q"].shape
+        flops = 3 * 2 * 2.0 * nb * Hq * (Lq * (Lq + 1) / 2) * Kq
+        from threadpoolctl import threadpool_info as tpi
+        threads = max([p.get("num_threads", 1) for p in tpi()] + [1])
+        return {"value": round(flops / dt / 1e12, 4), "unit": "TFLOP/s", "cores": threads, "kind": "oracle",
+                "sample": f"first {nb} of {cfg['q'].shape[0]} batch elements, forward + backward, fp64 "
+                          f"(numpy; {dt:.1f} s)"}
     x = NT(f64(cfg["x"][:nb]), (B, L, D))
     t0 = time.perf_counter()
     if workload in ("ffn", "ffn_bias"):

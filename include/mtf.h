@@ -311,6 +311,23 @@ int mtf_mha_bwd(const mtf_mha_dims* d, const void* x, const void* w_q, const voi
                 void* dw_q, void* dw_k, void* dw_v, void* dw_o, void* dx_partial,
                 void* workspace, size_t workspace_bytes, void* stream);
 
+/* The attention core alone, for any head width d_k = d_v divisible by 8 (the LM models of the
+ * paper use 256): ctx[batch,length,heads,d_k] = einsum(softmax_m(scale * einsum(q, k -> [batch,
+ * heads,length,memory])), v), lse[batch,heads,length] fp32; q, k, v, ctx, dctx, dq, dk, dv bf16
+ * [batch,length,heads,d_k].  d_k = 128 runs the fused kernels (no workspace forward); any other
+ * width runs the two einsums on the GEMM kernel with a row-softmax kernel between them and needs
+ * length % 8 == 0 and a workspace for the [batch,heads,length,length] intermediates.
+ * d->d_model is not used.  Errors: NULL, SIZE_MISMATCH, UNSUPPORTED, ALIGN, WORKSPACE, HIP. */
+size_t mtf_attention_fwd_workspace_bytes(const mtf_mha_dims* d);
+int mtf_attention_fwd(const mtf_mha_dims* d, const void* q, const void* k, const void* v,
+                      float scale, int causal, void* ctx, void* lse, void* workspace,
+                      size_t workspace_bytes, void* stream);
+size_t mtf_attention_bwd_workspace_bytes(const mtf_mha_dims* d);
+int mtf_attention_bwd(const mtf_mha_dims* d, const void* q, const void* k, const void* v,
+                      const void* ctx, const void* lse, const void* dctx, float scale, int causal,
+                      void* dq, void* dk, void* dv, void* workspace, size_t workspace_bytes,
+                      void* stream);
+
 /* Whole layer for a one-slice Allreduce group: u = x + MHA(x), z = u + FFN(u); u, z bf16. */
 typedef struct {
   const void *w_q, *w_k, *w_v, *w_o, *w_in, *w_out; /* device, bf16 */

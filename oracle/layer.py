@@ -106,20 +106,42 @@ def attention_probs(q, k_, scale, causal):
     return NT(e / tot, (B, H, L, M)), NT((mx + np.log(tot))[..., 0], (B, H, L))
 
 
-def mha_fwd(x, w_q, w_k, w_v, w_o, scale, causal, store=round_to_bf16):
-    """Self-attention: memory = x.  Returns q, k, v, ctx, lse (saved) and y [B,L,D]."""
-    x_m = _rename(x, L, M)
-    q = _st(einsum([x, w_q], (B, L, H, K)), store)
-    k_ = _st(einsum([x_m, w_k], (B, M, H, K)), store)
-    v_ = _st(einsum([x_m, w_v], (B, M, H, V)), store)
+def attention_core_fwd(q, k_, v_, scale, causal, store=round_to_bf16):
+    """ctx = einsum(softmax(scale * einsum(q, k_)), v_) and lse, from stored q, k_, v_."""
     e, tot, mx = _softmax_parts(q, k_, scale, causal)
     # ctx = einsum(p, v_) with p = e / tot.  The exponentials enter the contraction in
     # storage precision; the row sum that normalises them is taken before rounding.
     ctx_un = einsum([NT(store(e), (B, H, L, M)), v_], (B, L, H, V))
     inv = NT(1.0 / tot[..., 0], (B, H, L))
     ctx = _st(einsum([ctx_un, inv], (B, L, H, V)), store)
-    y = einsum([ctx, w_o], (B, L, D))
     lse = NT((mx + np.log(tot))[..., 0], (B, H, L))
+    return ctx, lse
+
+
+def attention_core_bwd(q, k_, v_, ctx, lse, dctx, scale, causal, store=round_to_bf16):
+    """Gradients w.r.t. q, k_, v_ given the (stored) dctx; probabilities are recomputed from the
+    logits and lse."""
+    s = einsum([q, k_], (B, H, L, M))
+    vis = _visible(s.data.shape[2], s.data.shape[3], causal)
+    p = NT(np.where(vis, np.exp(scale * s.data - lse.data[..., None]), 0.0), s.dims)
+    dp = einsum([dctx, v_], (B, H, L, M))
+    # softmax Jacobian: ds = p * (dp - sum_m p*dp); sum_m p*dp = sum_v dctx*ctx
+    delta = einsum([dctx, ctx], (B, H, L))
+    ds = _st(NT(scale * p.data * (dp.data - delta.data[..., None]), s.dims), store)
+    dv_ = _st(einsum([_st(p, store), dctx], (B, M, H, V)), store)
+    dq = _st(einsum([ds, k_], (B, L, H, K)), store)
+    dk_ = _st(einsum([ds, q], (B, M, H, K)), store)
+    return dq, dk_, dv_
+
+
+def mha_fwd(x, w_q, w_k, w_v, w_o, scale, causal, store=round_to_bf16):
+    """Self-attention: memory = x.  Returns q, k, v, ctx, lse (saved) and y [B,L,D]."""
+    x_m = _rename(x, L, M)
+    q = _st(einsum([x, w_q], (B, L, H, K)), store)
+    k_ = _st(einsum([x_m, w_k], (B, M, H, K)), store)
+    v_ = _st(einsum([x_m, w_v], (B, M, H, V)), store)
+    ctx, lse = attention_core_fwd(q, k_, v_, scale, causal, store)
+    y = einsum([ctx, w_o], (B, L, D))
     return dict(q=q, k=k_, v=v_, ctx=ctx, lse=lse, y=y)
 
 
@@ -131,16 +153,7 @@ def mha_bwd(x, w_q, w_k, w_v, w_o, q, k_, v_, ctx, lse, dy, scale, causal,
     dy = _st(dy, store)
     dw_o = einsum([ctx, dy], (H, V, D))
     dctx = _st(einsum([dy, w_o], (B, L, H, V)), store)
-    s = einsum([q, k_], (B, H, L, M))
-    vis = _visible(s.data.shape[2], s.data.shape[3], causal)
-    p = NT(np.where(vis, np.exp(scale * s.data - lse.data[..., None]), 0.0), s.dims)
-    dp = einsum([dctx, v_], (B, H, L, M))
-    # softmax Jacobian: ds = p * (dp - sum_m p*dp); sum_m p*dp = sum_v dctx*ctx
-    delta = einsum([dctx, ctx], (B, H, L))
-    ds = _st(NT(scale * p.data * (dp.data - delta.data[..., None]), s.dims), store)
-    dv_ = _st(einsum([_st(p, store), dctx], (B, M, H, V)), store)
-    dq = _st(einsum([ds, k_], (B, L, H, K)), store)
-    dk_ = _st(einsum([ds, q], (B, M, H, K)), store)
+    dq, dk_, dv_ = attention_core_bwd(q, k_, v_, ctx, lse, dctx, scale, causal, store)
     dw_q = einsum([x, dq], (D, H, K))
     dw_k = einsum([x_m, dk_], (D, H, K))
     dw_v = einsum([x_m, dv_], (D, H, V))

@@ -73,7 +73,7 @@ class MtfError(RuntimeError):
 
 lib.mtf_status_string.restype = C.c_char_p
 lib.mtf_last_error.restype = C.c_char_p
-for _f in ("mtf_ffn_bwd_workspace_bytes", "mtf_ffn_bias_bwd_workspace_bytes", "mtf_mha_bwd_workspace_bytes",
+for _f in ("mtf_attention_fwd_workspace_bytes", "mtf_attention_bwd_workspace_bytes", "mtf_ffn_bwd_workspace_bytes", "mtf_ffn_bias_bwd_workspace_bytes", "mtf_mha_bwd_workspace_bytes",
            "mtf_layer_fwd_workspace_bytes", "mtf_layer_bwd_workspace_bytes",
            "mtf_reduce_local_workspace_bytes"):
     if hasattr(lib, _f):
@@ -457,6 +457,29 @@ def mha_bwd(x, w_q, w_k, w_v, w_o, q, k, v, ctx, lse, dy, scale, causal, workspa
                            int(bool(causal)), _ptr(out["dw_q"]), _ptr(out["dw_k"]), _ptr(out["dw_v"]),
                            _ptr(out["dw_o"]), _ptr(out["dx"]), _ptr(ws), C.c_size_t(ws.numel()), _stream()))
     return out
+
+
+def attention_fwd(q, k, v, scale, causal):
+    """The attention core for any head width: q, k, v bf16 [batch, length, heads, d_k] -> (ctx, lse)."""
+    b, l, h, dk = q.shape
+    d = mtf_mha_dims(b, l, h * dk, h, dk)
+    ctx = torch.empty_like(q)
+    lse = torch.empty((b, h, l), dtype=torch.float32, device=q.device)
+    ws = _ws(lib.mtf_attention_fwd_workspace_bytes(C.byref(d)), q.device)
+    _check(lib.mtf_attention_fwd(C.byref(d), _ptr(q), _ptr(k), _ptr(v), C.c_float(scale), int(bool(causal)),
+                                 _ptr(ctx), _ptr(lse), _ptr(ws), C.c_size_t(ws.numel()), _stream()))
+    return ctx, lse
+
+
+def attention_bwd(q, k, v, ctx, lse, dctx, scale, causal):
+    b, l, h, dk = q.shape
+    d = mtf_mha_dims(b, l, h * dk, h, dk)
+    dq, dk_, dv = torch.empty_like(q), torch.empty_like(q), torch.empty_like(q)
+    ws = _ws(lib.mtf_attention_bwd_workspace_bytes(C.byref(d)), q.device)
+    _check(lib.mtf_attention_bwd(C.byref(d), _ptr(q), _ptr(k), _ptr(v), _ptr(ctx), _ptr(lse), _ptr(dctx),
+                                 C.c_float(scale), int(bool(causal)), _ptr(dq), _ptr(dk_), _ptr(dv), _ptr(ws),
+                                 C.c_size_t(ws.numel()), _stream()))
+    return dq, dk_, dv
 
 
 def _layer_dims(x, w):

@@ -32,6 +32,9 @@ struct GemmDesc {
   // optional: bias[n] (N values, 8-byte aligned) added to every row after alpha / accumulate and
   // before the epilogue: C = epi(alpha * sum + old C + bias).  Not with grouped launches.
   const bf16_t* bias = nullptr;
+  // optional: one fp32 factor per output row, row_scale[z * M + m] (z = batch index), applied to
+  // alpha * sum before accumulate / bias / epilogue (softmax normalisation of an attention row)
+  const float* row_scale = nullptr;
   float alpha = 1.f;
   bool accumulate = false;
   // batch: z = z0 * batch1 + z1

@@ -71,6 +71,7 @@ struct GemmArgs {
   void* C[kMaxGroup];
   const bf16_t* aux;
   const bf16_t* bias;
+  const float* row_scale;
   float alpha;
   int accumulate;
   int tiles_m[kMaxGroup], tiles_n[kMaxGroup];
@@ -413,6 +414,11 @@ __global__ void __launch_bounds__(Cfg::kThreads, Cfg::kWavesPerSimd) gemm_bf16_k
       if (m >= M || n >= N) continue;
       const int64_t idx = offC + (int64_t)m * ldc + n;
       float v[4] = {t[0], t[1], t[2], t[3]};
+      if (g.row_scale) {
+        const float rs = g.row_scale[(int64_t)zb * M + m];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] *= rs;
+      }
       if (g.accumulate) {
         if (OUT_BF16) {
           uint2 old = *reinterpret_cast<const uint2*>(static_cast<const bf16_t*>(Cg) + idx);
@@ -458,11 +464,16 @@ __global__ void __launch_bounds__(Cfg::kThreads, Cfg::kWavesPerSimd) gemm_bf16_k
 template <class Cfg, bool A_K, bool B_K, int EPI, bool OUT_BF16>
 int launch_instance(const GemmArgs& a, int batch, hipStream_t stream) {
   // name as a profiler prints the instantiation
-  static char name[96] = "";  // fits mtf_kernel_time::kernel
-  if (!name[0])
-    std::snprintf(name, sizeof name, "gemm_bf16_kernel<TileCfg<%d, %d, %d, %d, %d, %d>, %s, %s, %d, %s>", Cfg::BM,
-                  Cfg::BN, Cfg::WM, Cfg::WN, Cfg::kGroupM, Cfg::kStages, A_K ? "true" : "false", B_K ? "true" : "false", EPI,
-                  OUT_BF16 ? "true" : "false");
+  struct Name {
+    char text[96];  // fits mtf_kernel_time::kernel
+    Name() {
+      std::snprintf(text, sizeof text, "gemm_bf16_kernel<TileCfg<%d, %d, %d, %d, %d, %d>, %s, %s, %d, %s>", Cfg::BM,
+                    Cfg::BN, Cfg::WM, Cfg::WN, Cfg::kGroupM, Cfg::kStages, A_K ? "true" : "false",
+                    B_K ? "true" : "false", EPI, OUT_BF16 ? "true" : "false");
+    }
+  };
+  static const Name name_once;  // initialised once, also when two host threads launch at the same time
+  const char* name = name_once.text;
   GemmArgs args = a;
   int64_t tiles = 0;
   double flops = 0, bytes = 0;
@@ -522,6 +533,7 @@ bool gemm_bf16_supported(const GemmDesc& d) {
   }
   if (!aligned16(d.C) || (d.epi == MTF_EPI_MASK_GT0 && (!d.aux || !aligned16(d.aux)))) return false;
   if (d.bias && (((uintptr_t)d.bias & 7) || d.nextra > 0)) return false;
+  if (d.row_scale && d.nextra > 0) return false;
   if (d.batch0 * d.batch1 > 65535) return false;
   if (d.nextra < 0 || d.nextra > kMaxGroup - 1) return false;
   if (d.nextra > 0 && (d.nseg != 1 || d.batch0 * d.batch1 != 1 || d.accumulate || d.epi != MTF_EPI_NONE))
@@ -561,6 +573,7 @@ int gemm_bf16_launch(const GemmDesc& d, hipStream_t stream) {
   }
   a.aux = d.aux;
   a.bias = d.bias;
+  a.row_scale = d.row_scale;
   a.alpha = d.alpha;
   a.accumulate = d.accumulate ? 1 : 0;
   a.batch1 = (int)d.batch1;
