@@ -88,6 +88,30 @@ def test_edge_sizes(sizes):
         assert m1(f64(got), einsum(ins, "mn").data, einsum_abs(ins, "mn").data) <= 1e-5
 
 
+def test_largest_grids():
+    """The limits of the launch shapes: many tiles along m (thousands of tile rows through the
+    XCD remap), the largest batch count the grid takes, and one past it (generic kernel)."""
+    print("einsum_local tall: m=262144", flush=True)
+    sizes = dict(m=262144, n=136, k=72)
+    a, b = _rand("mk", torch.bfloat16, 21, sizes, ints=True), _rand("kn", torch.bfloat16, 22, sizes, ints=True)
+    got = mtf.einsum_local(a.cuda(), "mk", b.cuda(), "kn", "mn", out_dtype=torch.float32)
+    ref = a.float() @ b.float()                              # small integers: exact in any order
+    assert torch.equal(got.cpu(), ref)
+    # spot-check rows against the oracle's own einsum
+    rows = [0, 1, 255, 256, 131071, 131072, 262143]
+    ref_rows = einsum([named(a[rows], "mk"), named(b, "kn")], "mn").data
+    assert np.array_equal(f64(got[rows]), ref_rows)
+    for nb in (65535, 65536):
+        print(f"einsum_local batch {nb}", flush=True)
+        sizes = dict(b=nb, m=8, n=8, k=8)
+        a, b = _rand("bmk", torch.bfloat16, 23, sizes, ints=True), _rand("bkn", torch.bfloat16, 24, sizes, ints=True)
+        got = mtf.einsum_local(a.cuda(), "bmk", b.cuda(), "bkn", "bmn", out_dtype=torch.float32)
+        assert torch.equal(got.cpu(), torch.bmm(a.float(), b.float()))
+        pick = [0, 1, nb // 2, nb - 1]
+        ref = einsum([named(a[pick], "bmk"), named(b[pick], "bkn")], "bmn").data
+        assert np.array_equal(f64(got[pick]), ref)
+
+
 GENERIC_CASES = [
     ("fp32 matmul", "bld", "df", "blf", torch.float32),
     ("fp32 outer + reduce", "bm", "pn", "mn", torch.float32),
