@@ -361,7 +361,7 @@ def cpu_baseline(workload, cfg):
     from oracle.layer import B, L, D, F, H, K, V
 
     f64 = lambda t: t.double().numpy()
-    nb = 2                                           # batch elements in the sample
+    nb = 4 if workload == "layer" else 2             # batch elements in the sample (~10 s of host work)
     if workload == "vocab":
         return cpu_baseline_vocab(cfg, nb)
     if workload == "attention_lm":

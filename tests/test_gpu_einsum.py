@@ -112,6 +112,43 @@ def test_largest_grids():
         assert np.array_equal(f64(got[pick]), ref)
 
 
+def test_seeded_sweep_of_shapes_layouts_and_epilogues():
+    """40 seeded random problems: sizes that are and are not multiples of the tile sizes, every
+    operand layout, batches, output dtype, ReLU / bias / alpha / accumulate, all against the
+    oracle.  Whatever does not fit the MFMA kernel must run on the generic one with the same
+    result."""
+    rng = np.random.default_rng(18110208)
+    layouts = [("mk", "kn"), ("mk", "nk"), ("km", "kn"), ("km", "nk"), ("bmk", "bkn"), ("bmk", "bnk")]
+    for case in range(40):
+        da, db = layouts[rng.integers(len(layouts))]
+        do = ("b" if "b" in da else "") + ("mn" if rng.random() < 0.8 else "nm")
+        mult = 8 if rng.random() < 0.8 else 1
+        sizes = dict(m=int(rng.integers(1, 60)) * mult, n=int(rng.integers(1, 60)) * mult,
+                     k=int(rng.integers(1, 50)) * mult, b=int(rng.integers(1, 4)))
+        out_dtype = torch.float32 if rng.random() < 0.5 else torch.bfloat16
+        alpha = float(rng.choice([1.0, 0.5, -2.0]))
+        epi = [mtf.EPI_NONE, mtf.EPI_RELU, mtf.EPI_BIAS, mtf.EPI_BIAS_RELU][rng.integers(4)]
+        accumulate = bool(rng.random() < 0.3)
+        print(f"sweep {case}: {da},{db}->{do} {sizes} {out_dtype} alpha={alpha} epi={epi} acc={accumulate}", flush=True)
+        a, b = _rand(da, torch.bfloat16, 100 + case, sizes), _rand(db, torch.bfloat16, 200 + case, sizes)
+        ref = alpha * einsum([named(a, da), named(b, db)], do).data
+        out = None
+        if accumulate:
+            old = _rand(do, out_dtype, 300 + case, sizes)
+            ref = ref + f64(old)
+            out = old.cuda().clone()
+        aux = None
+        if epi in (mtf.EPI_BIAS, mtf.EPI_BIAS_RELU):
+            aux = _rand(do[-1], torch.bfloat16, 400 + case, sizes)
+            ref = ref + f64(aux)                                  # broadcast over the leading dims
+        if epi in (mtf.EPI_RELU, mtf.EPI_BIAS_RELU):
+            ref = np.maximum(ref, 0.0)
+        got = mtf.einsum_local(a.cuda(), da, b.cuda(), db, do, out_dtype=out_dtype, epi=epi,
+                               aux=aux.cuda() if aux is not None else None, alpha=alpha, accumulate=accumulate, out=out)
+        want = round_to_bf16(ref) if out_dtype == torch.bfloat16 else ref
+        assert m2(f64(got), want) <= BF16_TOL, case
+
+
 GENERIC_CASES = [
     ("fp32 matmul", "bld", "df", "blf", torch.float32),
     ("fp32 outer + reduce", "bm", "pn", "mn", torch.float32),
