@@ -21,8 +21,14 @@
  *     through `workspace` arguments sized by the mtf_*_workspace_bytes() calls.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Device calls
  *     are asynchronous on it; the library never synchronises.
- *   - Host-only calls (mtf_slice, mtf_einsum_plan, rank/coord helpers, *_workspace_bytes,
- *     mtf_status_string) touch no GPU and work on a machine without one.
+ *   - Host-only calls (mtf_slice, mtf_einsum_plan, mtf_reshape_plan, rank/coord helpers,
+ *     *_workspace_bytes, mtf_status_string) touch no GPU and work on a machine without one.
+ *
+ * Contents: slices and lowering plans (host); slice gather, the local einsum with its fused
+ * epilogues, partial-sum reduce (the Allreduce stand-in on a virtual mesh); component-wise
+ * addition with implicit broadcasting, local reductions; reshape on a virtual mesh; the
+ * vocabulary-split operations; fixed steps of the model-parallel Transformer layer (feed-forward
+ * with and without bias, attention core, multi-head attention, whole layer); measurement aids.
  */
 #ifndef MTF_H_
 #define MTF_H_
