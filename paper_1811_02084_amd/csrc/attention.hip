@@ -236,7 +236,7 @@ __device__ __forceinline__ QueryRows query_rows(int length, bool causal, int wav
 // One workgroup: NWAVES*32 query rows of one (batch, head); each wave owns 32 of them.
 template <int NWAVES>
 // second launch-bound argument: wavefronts per SIMD the register budget must allow
-__global__ void __launch_bounds__(NWAVES * 64, 2) attn_fwd_kernel(AttnArgs a) {
+__global__ void __launch_bounds__(NWAVES * 64, NWAVES >= 4 ? 2 : 1) attn_fwd_kernel(AttnArgs a) {
   __shared__ __attribute__((aligned(1024))) char stage0[2 * kTileBytes];  // K tile, V tile
   __shared__ __attribute__((aligned(1024))) char stage1[2 * kTileBytes];
   // Slabs: with 8 waves they need as much LDS as both stages, and get their own (one workgroup
@@ -383,7 +383,7 @@ __global__ void __launch_bounds__(NWAVES * 64, 2) attn_fwd_kernel(AttnArgs a) {
 // delta[b,h,l] = sum_d dctx[b,l,h,d] * ctx[b,l,h,d] (= sum_m p * dp of the softmax Jacobian) for
 // its rows, which the dk/dv kernel launched after it reads.
 template <int NWAVES>
-__global__ void __launch_bounds__(NWAVES * 64, 2) attn_dq_kernel(AttnArgs a) {
+__global__ void __launch_bounds__(NWAVES * 64, NWAVES >= 4 ? 2 : 1) attn_dq_kernel(AttnArgs a) {
   __shared__ __attribute__((aligned(1024))) char stage0[2 * kTileBytes];  // K tile, V tile
   __shared__ __attribute__((aligned(1024))) char stage1[2 * kTileBytes];
   constexpr bool kOwnSlabs = NWAVES == 8;  // as in the forward kernel

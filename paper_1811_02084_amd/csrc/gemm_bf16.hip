@@ -52,7 +52,9 @@ struct TileCfg {
   static constexpr int kStages = STAGES_;   // k-tiles resident in LDS (one computing, the rest in flight)
   // k-steps (of 16) of fragments fetched ahead; kFragAhead + 1 must divide the steps per k-tile
   static constexpr int kFragAhead = TM * TN >= 8 ? 1 : 3;
-  static constexpr int kWavesPerSimd = 2;  // register budget: two wavefronts per SIMD
+  // register budget: two wavefronts per SIMD where the LDS lets two workgroups of 4 waves (or one
+  // of 8) share a CU, else one
+  static constexpr int kWavesPerSimd = (kWaves == 4 && kStages * kStage > 80 * 1024) ? 1 : 2;
 };
 using LargeTile = TileCfg<256, 256, 2, 4, 4, 2>;      // 128 KiB LDS, one workgroup per CU
 using SmallTile = TileCfg<128, 128, 2, 2, 8, 2>;      // 64 KiB LDS, two workgroups per CU
