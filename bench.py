@@ -43,6 +43,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="layer", choices=["layer", "ffn", "ffn_bias", "mha", "attention_lm", "vocab", "reshape", "copy"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--graph", action="store_true",
+                    help="time replays of one captured HIP graph of the step instead of eager launches")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (one processor's share of the mesh); "
@@ -163,11 +165,19 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    run_step = step
+    if args.graph:                   # the library allocates nothing and never synchronises: capturable
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step()
+        run_step = graph.replay
+        run_step()
+        torch.cuda.synchronize()
     gc.collect()
     gc.disable()                     # as timeit does: no collector pause of the host inside the timed region
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        step()
+        run_step()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     gc.enable()
@@ -227,7 +237,7 @@ def main():
         "metric": METRIC, "value": round(tflops, 2), "unit": "TFLOP/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
-        "data": "synthetic",
+        "data": "synthetic", "launch": "hipGraph replay" if args.graph else "eager",
         "config": {"workload": name, "flop_per_step": step_flops,
                    "flop_counting": "2 x iteration-space size per einsum, causal pairs only"},
         "frac_of_bf16_mfma_peak": round(tflops / PEAK_BF16_TFLOPS, 4),
