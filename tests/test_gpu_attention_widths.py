@@ -31,6 +31,10 @@ CASES = [  # batch, length, heads, d_k, causal
     (3, 200, 2, 32, False),
     (2, 72, 2, 128, True),       # the fused kernels behind the same entry points
     (4, 256, 8, 256, True),      # a shard of the LM variant: 8 heads of width 256
+    (4, 200, 32, 128, True),     # fused kernels with 4 waves per workgroup (128 (batch, head) pairs), ragged
+    (4, 256, 32, 128, False),
+    (4, 384, 32, 128, True),     # 8-wave workgroups with an odd number of 128-row blocks (middle block unpaired)
+    (4, 328, 32, 128, False),    # the same, ragged and unmasked
 ]
 
 
