@@ -17,7 +17,13 @@
 //   * the MFMA is issued with its operands exchanged (B-fragment as the instruction's A), which
 //     leaves every lane holding 4 consecutive n of one row m; the epilogue transposes 32x64 slabs
 //     through LDS so that global stores (and aux / old-C loads) are contiguous 256 B row pieces;
-//   * out-of-range chunks (ragged M, N, K) are fetched from a 16-byte block of zeros instead;
+//   * fragments are fetched from LDS ahead of the MFMAs that use them, in an order pinned by
+//     scheduling barriers, and the fetch-ahead runs across k-tile boundaries (the barrier that
+//     publishes the next k-tile stands where a wave has fetched its last fragment of this one);
+//   * ragged M / N: rows past the edge are clamped to the last row at load time (they only reach
+//     outputs that are not stored); ragged K: chunks past K are zero-filled in LDS;
+//   * one launch can sum up to 3 (A, B, K) segments into one C, or run up to 4 independent
+//     problems (grouped launch), so that small outputs still fill the chip;
 //   * workgroup ids are dealt round-robin to the 8 XCDs by hardware, so ids are remapped to make
 //     each XCD (own L2) work on a compact patch of C.
 #include "gemm_bf16.h"
