@@ -13,6 +13,14 @@
 // LDS tiles are 64 rows x 128 d (256 B per row), filled by direct global->LDS loads.  One XOR
 // swizzle of the 16-byte chunk index serves both access patterns (row-wise ds_read_b128 and
 // transposed ds_read_b64_tr_b16).
+//
+// Work decomposition: a wave owns 32 query rows (forward, dq) or 32 memory rows (dk/dv) and keeps
+// their operand fragments in registers for the whole kernel; those fragments arrive, and the
+// results leave, through wave-private LDS slabs so that global memory sees whole 256-byte rows.
+// Under the causal mask an 8-wave workgroup pairs a late with an early block of query rows, and
+// grids put heads fastest, so that every SIMD and every XCD gets the same amount of work.
+// The softmax keeps the vector ALU work per logit at one fma, one exp2 and one add (scale folded
+// into the fma, running maximum raised lazily, masking only on ragged / diagonal tiles).
 #include "attention.h"
 
 #include "timing.h"
