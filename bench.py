@@ -5,7 +5,7 @@ One step = one pass of the whole hot path over one batch of synthetic input: for
 backward of a full Transformer-layer shard (attention + feed-forward sublayers with their
 residual adds), every contraction in the library's HIP kernels.  Prints ONE JSON line.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload layer|ffn|ffn_bias|mha|attention_lm|vocab|reshape]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload layer|ffn|ffn_bias|mha|mesh|attention_lm|vocab|reshape]
 
 `--workload copy` is not a benchmark of the path: it launches the library's plain copy kernel
 (fp32 -> fp32 cast) on a buffer of known size, which is what the HBM counters of a profiler run
@@ -41,7 +41,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="layer", choices=["layer", "ffn", "ffn_bias", "mha", "attention_lm", "vocab", "reshape", "copy"])
+    ap.add_argument("--workload", default="layer", choices=["layer", "ffn", "ffn_bias", "mha", "mesh", "attention_lm", "vocab", "reshape", "copy"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--graph", action="store_true",
                     help="time replays of one captured HIP graph of the step instead of eager launches")
@@ -109,6 +109,25 @@ def main():
             def step():
                 a, _ = mtf.ffn_bias_fwd(g["x"], g["w_in"], bias, g["w_out"])
                 mtf.ffn_bias_bwd(g["x"], a, g["w_in"], g["w_out"], g["dy"], workspace=ws)
+    elif args.workload == "mesh":
+        # config 4: the feed-forward sublayer on a VIRTUAL 4x4 mesh held on this one GPU (batch over
+        # rows, d_ff over cols): 16 processors' local einsums, then the partial sums "summed up by
+        # processor-column" - 4 groups of 4 - by the reduce kernel that stands in for the Allreduce
+        cfg = mtf_inputs.config4()
+        mesh, layout = cfg["mesh"], cfg["layout"]
+        B, L, D = cfg["x"].shape
+        F = cfg["w_in"].shape[1]
+        fwd = flops_ffn(B * L, D, F) / 3.0                        # forward only: undo the x3 below
+        name = f"config 4: FFN forward on a virtual 4x4 mesh, x[{B},{L},{D}] d_ff={F}, 16 slices + 4 group reduces"
+        g = {k: v.to(dev) for k, v in cfg.items() if torch.is_tensor(v)}
+        coords = [(r, c) for r in range(4) for c in range(4)]
+        xs = {c: mtf.slice_copy(g["x"], ("batch", "length", "d_model"), mesh, layout, c) for c in coords}
+        wi = {c: mtf.slice_copy(g["w_in"], ("d_model", "d_ff"), mesh, layout, c) for c in coords}
+        wo = {c: mtf.slice_copy(g["w_out"], ("d_ff", "d_model"), mesh, layout, c) for c in coords}
+
+        def step():
+            parts = {c: mtf.ffn_fwd(xs[c], wi[c], wo[c])[1] for c in coords}
+            return [mtf.reduce_partials([parts[(r, c)] for c in range(4)]) for r in range(4)]
     elif args.workload == "attention_lm":
         # the attention core at the head width of the paper's language models (d_k = d_v = 256):
         # 8 local heads of width 256 (the same 2048 columns as config 5), causal, 8 x 512 tokens
@@ -371,9 +390,19 @@ def cpu_baseline(workload, cfg):
     from oracle.layer import B, L, D, F, H, K, V
 
     f64 = lambda t: t.double().numpy()
-    nb = 4 if workload == "layer" else 2             # batch elements in the sample (~10 s of host work)
+    nb = {"layer": 4, "mesh": 64}.get(workload, 2)   # batch elements in the sample (~5-10 s of host work)
     if workload == "vocab":
         return cpu_baseline_vocab(cfg, nb)
+    if workload == "mesh":                           # the unsplit forward on the first batch elements
+        w_in, w_out = NT(f64(cfg["w_in"]), (D, F)), NT(f64(cfg["w_out"]), (F, D))
+        xm = NT(f64(cfg["x"][:nb]), (B, L, D))
+        t0 = time.perf_counter()
+        OL.ffn_fwd(xm, w_in, w_out)
+        dt = time.perf_counter() - t0
+        flops = flops_ffn(nb * cfg["x"].shape[1], cfg["x"].shape[2], cfg["w_in"].shape[1])
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        return {"value": round(flops / dt / 1e12, 4), "unit": "TFLOP/s", "cores": threads, "kind": "oracle",
+                "sample": f"first {nb} of {cfg['x'].shape[0]} batch elements, unsplit forward, fp64 (numpy; {dt:.1f} s)"}
     if workload == "attention_lm":
         from oracle import layer as OLA
         from oracle.einsum import NT as NTA
