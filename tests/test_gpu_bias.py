@@ -221,3 +221,28 @@ def test_example_on_the_three_dimensional_layout(mtf):
         offs, locs = slice_spec((B, L, D), full["y"].data.shape, mesh, layout, c)
         idx = tuple(slice(o, o + n) for o, n in zip(offs, locs))
         assert np.array_equal(y.double().cpu().numpy(), full["y"].data[idx]), c
+
+
+def test_seeded_sweep_of_reductions_and_broadcasts(mtf):
+    """Random ranks, sizes, kept dims and output orders: every kernel pattern (columns, rows,
+    generic; vector and scalar runs) against the oracle."""
+    rng = np.random.Generator(np.random.Philox(key=[mtf_inputs.BASE_SEED, 61]))
+    names = ["p", "q", "r", "s"]
+    for case in range(30):
+        rank = int(rng.integers(1, 5))
+        dims = tuple(names[:rank])
+        shape = tuple(int(rng.choice([1, 3, 8, 24, 40, 130])) for _ in dims)
+        keep = [d for d in dims if rng.random() < 0.5]
+        rng.shuffle(keep)
+        dtype = torch.bfloat16 if rng.random() < 0.5 else torch.float32
+        print(f"sweep {case}: {dict(zip(dims, shape))} keep {keep} {dtype}", flush=True)
+        x = mtf_inputs.small_ints(26, case, shape, dtype=dtype)
+        ref = to_nt(x, dims)
+        for op, name in ((mtf.REDUCE_SUM, "sum"), (mtf.REDUCE_MAX, "max")):
+            got = mtf.reduce_local(_dev(x), dims, tuple(keep), op)
+            want = o_reduce(ref, tuple(keep), name).data
+            assert np.array_equal(got.double().cpu().numpy().reshape(want.shape), want), (case, name)
+        if keep:
+            b = mtf_inputs.small_ints(27, case, tuple(dict(zip(dims, shape))[d] for d in keep), dtype=dtype)
+            got = mtf.add_broadcast(_dev(x), dims, _dev(b), tuple(keep))
+            assert np.array_equal(got.double().cpu().numpy(), o_add(ref, to_nt(b, tuple(keep))).data), case

@@ -61,3 +61,40 @@ def test_reshape_errors(mtf):
     with pytest.raises(mtf.MtfError) as e:
         mtf.reshape_plan([("a", 4), ("b", 6)], [("c", 4), ("hidden", 6)], [("all", 4)], [("hidden", "all")])
     assert e.value.name == "MTF_ERR_INDIVISIBLE"
+
+
+def test_seeded_sweep_of_reshapes(mtf):
+    """Random ranks and name assignments on two meshes: whatever the oracle accepts must come out
+    bit-exact on every processor; whatever it rejects the library must reject with the same code."""
+    rng = np.random.Generator(np.random.Philox(key=[mtf_inputs.BASE_SEED, 71]))
+    meshes = [([("all", 4)], [("batch", "all"), ("hidden", "all"), ("vocab", "all")]),
+              ([("rows", 2), ("cols", 3)], [("batch", "rows"), ("hidden", "cols"), ("vocab", "cols"), ("z", "rows")])]
+    pool = ["batch", "hidden", "vocab", "z", "a", "b", "c", "d"]
+    done = 0
+    for case in range(60):
+        mesh, layout = meshes[case % 2]
+        rank = int(rng.integers(1, 4))
+        in_dims = tuple(rng.choice(pool, size=rank, replace=False))
+        out_dims = tuple(rng.choice(pool, size=rank, replace=False))
+        sizes = tuple(int(rng.choice([12, 24, 36])) for _ in range(rank))
+        in_shape, out_shape = list(zip(in_dims, sizes)), list(zip(out_dims, sizes))
+        try:
+            plan = reshape_plan(in_dims, out_dims, sizes, mesh, layout)
+        except Exception as e:
+            with pytest.raises(mtf.MtfError) as got:
+                mtf.reshape_plan(in_shape, out_shape, mesh, layout)
+            assert got.value.name == "MTF_ERR_" + e.code, (case, in_dims, out_dims)
+            continue
+        print(f"sweep {case}: {in_dims}->{out_dims} {sizes} on {mesh}: {plan}", flush=True)
+        assert mtf.reshape_plan(in_shape, out_shape, mesh, layout) == plan
+        t = mtf_inputs.normal(42, case, sizes, dtype=torch.float32)
+        want = lowered_reshape(nt(t.double().numpy(), in_dims), out_dims, mesh, layout)
+        coords = all_coords(mesh)
+        slices = [None] * len(coords)
+        for c in coords:
+            slices[coord_to_rank(mesh, c)] = mtf.slice_copy(t.cuda(), in_dims, mesh, layout, c)
+        for c in coords:
+            got = mtf.reshape_virtual(slices, in_shape, out_shape, mesh, layout, c)
+            assert np.array_equal(got.double().cpu().numpy(), want[c].data), (case, c)
+        done += 1
+    assert done >= 20
