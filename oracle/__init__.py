@@ -14,13 +14,15 @@ Modules
   layer    feed-forward and multi-head-attention sublayers of the model-parallel
            Transformer (section 'Model-Parallel "Transformer"'), forward and backward,
            written as sequences of the named einsum
-  metrics  the two error measures the parity tests gate on
+  metrics  the error measures the parity tests gate on
 
 Pins (see tests/test_oracle_*.py): brute-force loops on tiny inputs, closed forms
 (all-ones), exact integer evaluation, slice shapes and per-processor element counts the
 paper prints (worked example and Table 1), the layout-independence statement of the
 worked example, Appendix B's two ratios, finite differences and the adjoint identity for
-every backward function, closed forms of softmax attention.
+every backward function, closed forms of softmax attention; the error measures of metrics by
+hand-computed vectors; the library-backed large-size einsum path against the written-out
+definition at sizes where the library re-orders the contraction.
 
 Parity unpinned: the layer *semantics* relative to the authors' own Transformer code
 (attention scale, mask constant, absence of layer norm / dropout / bias).  The paper

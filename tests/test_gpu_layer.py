@@ -13,7 +13,7 @@ import paper_1811_02084_amd as mtf
 from oracle import layer as OL
 from oracle import layout as OLY
 from oracle.einsum import NT
-from oracle.metrics import m2
+from oracle.metrics import m2, rel_l2
 from helpers import f64, named, to_dev, on_device, BF16_TOL, F32_TOL, WEIGHT_DIMS
 from oracle.layer import B, L, D, F, H, K, V
 
@@ -49,7 +49,10 @@ def test_ffn_config2_full_size():
     _ffn_case(mtf_inputs.config2(), "config 2")
 
 
-def _mha_case(cfg, causal, label):
+LSE_TOL = 1e-3       # lse is an fp32 statistic of logits built from bf16 q, k (see _mha_case)
+
+
+def _mha_case(cfg, causal, label, exact_gate=False):
     print(f"MHA {label} causal={causal}", flush=True)
     g = on_device(cfg)
     x = named(cfg["x"], (B, L, D))
@@ -59,7 +62,17 @@ def _mha_case(cfg, causal, label):
     got = mtf.mha_fwd(g["x"], g["w_q"], g["w_k"], g["w_v"], g["w_o"], cfg["scale"], causal)
     for k in ("q", "k", "v", "ctx", "y"):
         _check(k, got[k], ref[k])
-    _check("lse", got["lse"], ref["lse"], 1e-3)
+    # lse = max + log(sum exp): fp32 on the device from fp32-accumulated logits of magnitude <= ~10,
+    # i.e. absolute errors of a few 1e-6 x |logit| plus exp2/log2 approximations (~1e-6 relative);
+    # gated two orders of magnitude below the bf16 bound and well above that arithmetic
+    _check("lse", got["lse"], ref["lse"], LSE_TOL)
+    if exact_gate:
+        # parity must not rest on the oracle's choice of rounding points alone: the same outputs
+        # against exact mathematics (no storage rounding anywhere in the oracle), same bound
+        exact = OL.mha_fwd(x, w["w_q"], w["w_k"], w["w_v"], w["w_o"], cfg["scale"], causal, OL.identity)
+        for k in ("ctx", "y"):
+            _check(k + " vs exact mathematics", got[k], exact[k])
+        _check("lse vs exact mathematics", got["lse"], exact["lse"], LSE_TOL)
     refb = OL.mha_bwd(x, w["w_q"], w["w_k"], w["w_v"], w["w_o"], ref["q"], ref["k"], ref["v"], ref["ctx"],
                       ref["lse"], dy, cfg["scale"], causal)
     sv = {k: to_dev(ref[k], torch.bfloat16) for k in ("q", "k", "v", "ctx")}
@@ -81,7 +94,7 @@ def test_mha_single_position_and_one_tile_edge():
 
 def test_mha_config3_full_size():
     cfg = mtf_inputs.config3()
-    _mha_case(cfg, cfg["causal"], "config 3")
+    _mha_case(cfg, cfg["causal"], "config 3", exact_gate=True)
 
 
 def test_attention_closed_forms_on_device():
@@ -99,7 +112,7 @@ def test_attention_closed_forms_on_device():
         assert np.max(np.abs(lse - want_lse[None, None, :])) <= 1e-4
 
 
-def _layer_case(cfg, causal, label):
+def _layer_case(cfg, causal, label, exact_gate=False):
     print(f"LAYER {label}", flush=True)
     g = on_device(cfg)
     w = {k: g[k] for k in WEIGHT_DIMS}
@@ -111,6 +124,13 @@ def _layer_case(cfg, causal, label):
     _check("z", z, ref["z"])
     for k in ("q", "k", "v", "ctx", "u", "a"):
         _check("saved " + k, bufs["saved"][k], ref["saved"][k])
+    _check("saved lse", bufs["saved"]["lse"], ref["saved"]["lse"], LSE_TOL)
+    if exact_gate:
+        # the same outputs against exact mathematics (oracle without any storage rounding)
+        exact = OL.layer_fwd(x, wn, cfg["scale"], causal, OL.identity)
+        _check("z vs exact mathematics", z, exact["z"])
+        _check("ctx vs exact mathematics", bufs["saved"]["ctx"], exact["saved"]["ctx"])
+        _check("u vs exact mathematics", bufs["saved"]["u"], exact["saved"]["u"])
     saved = {k: to_dev(v, torch.float32 if k == "lse" else torch.bfloat16) for k, v in ref["saved"].items()}
     dx = mtf.layer_bwd(g["x"], w, saved, g["dz"], cfg["scale"], causal, bufs)
     refb = OL.layer_bwd(x, wn, ref["saved"], dz, cfg["scale"], causal)
@@ -120,9 +140,19 @@ def _layer_case(cfg, causal, label):
     # one step with the device's own saved tensors (what the benchmark runs) must also work and,
     # the saved tensors agreeing to tolerance, give the same gradients to tolerance
     mtf.layer_fwd(g["x"], w, cfg["scale"], causal, bufs)
-    mtf.layer_bwd(g["x"], w, bufs["saved"], g["dz"], cfg["scale"], causal, bufs)
-    _check("dw_o (device-saved)", bufs["grads"]["dw_o"], refb["dw_o"])
-    _check("dw_out (device-saved)", bufs["grads"]["dw_out"], refb["dw_out"])
+    dx = mtf.layer_bwd(g["x"], w, bufs["saved"], g["dz"], cfg["scale"], causal, bufs)
+    _check("dx (device-saved)", dx, refb["dx"])
+    for k in ("dw_q", "dw_k", "dw_v", "dw_o", "dw_out"):
+        _check(k + " (device-saved)", bufs["grads"][k], refb[k])
+    # dw_in = einsum(u, da * [a > 0]): here the ReLU mask is decided by the device's own `a`, which
+    # differs from the oracle's at the few positions whose pre-activation is within rounding of 0.
+    # There a whole term u[t, :] * da[t, f] appears or disappears in column f - not small next to a
+    # sum of only a few thousand tokens - so the element-wise maximum is not the measure; the
+    # relative l2 error is held to the same bound.  (With the oracle's `a` on both sides, above,
+    # dw_in meets the element-wise bound.)
+    err = rel_l2(f64(bufs["grads"]["dw_in"]), refb["dw_in"].data)
+    print(f"    dw_in (device-saved): relative l2 err {err:.3e}", flush=True)
+    assert err <= BF16_TOL
 
 
 def test_layer_small_ragged():
@@ -131,7 +161,7 @@ def test_layer_small_ragged():
 
 def test_layer_config5_full_size():
     cfg = mtf_inputs.config5()
-    _layer_case(cfg, cfg["causal"], "config 5")
+    _layer_case(cfg, cfg["causal"], "config 5", exact_gate=True)
 
 
 def test_rejected_shapes():

@@ -8,8 +8,9 @@ import torch
 import mtf_inputs
 from helpers import named as to_nt
 from oracle import vocab as OV
-from oracle.einsum import nt
-from oracle.layout import all_coords, slice_spec
+from oracle.einsum import NT, nt
+from oracle.einsum import add_broadcast as o_add, einsum as o_einsum, reduce as o_reduce
+from oracle.layout import all_coords, slice_spec, slice_tensor
 from oracle.metrics import m2
 from oracle.vocab import B, L, D, VOCAB
 
@@ -32,7 +33,10 @@ def _dev(t):
 CASES = {
     "ragged-small": dict(batch=3, length=37, d_model=72, vocab_local=200, vocab_total=600, offset=200),
     "whole-vocab": dict(batch=2, length=50, d_model=264, vocab_local=328, vocab_total=328, offset=0),
-    "config6-size": dict(batch=16, length=256, d_model=1024, vocab_local=2048, vocab_total=32768, offset=2048),
+    # the stripe of config 6 at its real shape (16 x 256 tokens, d_model 1024, ids 2048 .. 4095); the
+    # oracle needs the whole vocabulary, so the group here is 2 processors instead of 16 (nothing the
+    # processor computes depends on how many others there are)
+    "config6-size": dict(batch=16, length=256, d_model=1024, vocab_local=2048, vocab_total=4096, offset=2048),
 }
 
 
@@ -70,52 +74,67 @@ def test_embedding_gradient_with_repeated_tokens_is_exact_on_integers(mtf):
     assert np.array_equal(got.double().cpu().numpy(), want[1:6])
 
 
+def _stripe_problem(cfg, p):
+    """The full-vocabulary problem whose processor `c` holds this stripe: the output-layer weight
+    is the stripe's columns and zero elsewhere, laid out over a mesh of vocab_total / vocab_local
+    processors with vocab split across it.  Zero columns elsewhere make this processor's partial
+    sum of dx the whole dx, so every gradient the device produces has an oracle counterpart."""
+    vt, vl, off = p["vocab_total"], p["vocab_local"], p["offset"]
+    w_full = np.zeros((cfg["w_vocab"].shape[0], vt))
+    w_full[:, off:off + vl] = cfg["w_vocab"].double().numpy()
+    mesh, layout = [("all", vt // vl)], [("vocab", "all")]
+    return nt(w_full, (D, VOCAB)), mesh, layout, (off // vl,)
+
+
 @pytest.mark.parametrize("case", sorted(CASES))
 def test_loss_stripe_forward_backward(mtf, case):
-    """One processor's stripe: its local statistics against the oracle's on the same stripe, then
-    (whole-vocab case) the loss itself, then the logits gradient and the two gradient einsums."""
+    """One processor's stripe of the output layer.  Every expected value is produced by the oracle
+    (oracle.vocab.xent_fwd / xent_bwd on the full vocabulary, the stripe taken with the oracle's
+    own slicing; the per-stripe statistics with the oracle's reduce / add_broadcast / einsum)."""
     p = CASES[case]
+    print(f"vocab stripe {case}", flush=True)
     cfg = mtf_inputs.vocab_inputs(33, p["batch"], p["length"], p["d_model"], p["vocab_local"], p["vocab_total"])
-    off, vl = p["offset"], p["vocab_local"]
-    x, w = to_nt(cfg["x"], (B, L, D)), to_nt(cfg["w_vocab"], (D, VOCAB))
-    z_ref = x.data @ w.data                                              # [b, l, vocab_local], fp64
+    off, vl, vt = p["offset"], p["vocab_local"], p["vocab_total"]
+    x = to_nt(cfg["x"], (B, L, D))
+    w_full, mesh, layout, c = _stripe_problem(cfg, p)
+    targets = cfg["targets"].numpy()
+    full = OV.xent_fwd(x, w_full, targets)
+    z_ref = slice_tensor(full["logits"], mesh, layout, c)                # [b, l, vocab_local]
     z = mtf.einsum_local(_dev(cfg["x"]), (B, L, D), _dev(cfg["w_vocab"]), (D, VOCAB), (B, L, VOCAB),
                          out_dtype=torch.float32)
-    assert m2(z.cpu().numpy(), z_ref) <= TOL_BF16
-    # the statistics kernels are fed the ORACLE's logits (stored fp32), so that every expected
-    # value below comes from the oracle side alone
-    z = _dev(torch.from_numpy(z_ref).float())
-    zd = z.double().cpu().numpy()
+    assert m2(z.cpu().numpy(), z_ref.data) <= TOL_BF16
+    # the statistics kernels are fed the ORACLE's logits (stored fp32) and the oracle's group-wide
+    # row maximum, so that every expected value below comes from the oracle side alone
+    z = _dev(torch.from_numpy(z_ref.data).float())
+    z_st = NT(z.double().cpu().numpy(), z_ref.dims)                       # what the device reads
     m_loc = mtf.reduce_local(z, (B, L, VOCAB), (B, L), mtf.REDUCE_MAX)
-    assert np.array_equal(m_loc.double().cpu().numpy(), zd.max(axis=-1))
-    targets = cfg["targets"]
-    sumexp, picked = mtf.xent_stats_local(z, m_loc, _dev(targets), off)
-    want_s = np.exp(zd - zd.max(axis=-1, keepdims=True)).sum(axis=-1)
-    tl = targets.numpy().astype(np.int64) - off
-    local = (tl >= 0) & (tl < vl)
-    want_t = np.where(local, np.take_along_axis(zd, np.clip(tl, 0, vl - 1)[..., None], axis=-1)[..., 0], 0.0)
-    assert m2(sumexp.cpu().numpy(), want_s) <= TOL_F32
-    assert np.array_equal(picked.double().cpu().numpy(), want_t)
-    if p["vocab_total"] == vl:                                           # the group is this one processor
-        loss = mtf.xent_loss(m_loc, sumexp, picked)
-        want = zd.max(axis=-1) + np.log(want_s) - want_t
-        assert m2(loss.cpu().numpy(), want) <= TOL_F32
-        full = OV.xent_fwd(x, w, targets.numpy())                        # and against the oracle end to end
+    assert np.array_equal(m_loc.double().cpu().numpy(), o_reduce(z_st, (B, L), "max").data)
+    m_grp = _dev(torch.from_numpy(full["m"].data).float())
+    m_st = NT(m_grp.double().cpu().numpy(), (B, L))
+    sumexp, picked = mtf.xent_stats_local(z, m_grp, _dev(cfg["targets"]), off)
+    want_s = o_reduce(NT(np.exp(o_add(z_st, NT(-m_st.data, m_st.dims)).data), z_st.dims), (B, L), "sum")
+    want_t = o_einsum([slice_tensor(OV.onehot(targets, vt), mesh, layout, c), z_st], (B, L))
+    assert m2(sumexp.cpu().numpy(), want_s.data) <= TOL_F32
+    assert np.array_equal(picked.double().cpu().numpy(), want_t.data)
+    if vt == vl:                                                         # the group is this one processor
+        loss = mtf.xent_loss(m_grp, sumexp, picked)
         assert m2(loss.cpu().numpy(), full["loss"].data) <= TOL_F32
-    # backward from given (group-wide) statistics
-    dloss = cfg["dloss"]
-    dz = mtf.xent_grad_local(z, m_loc, sumexp, _dev(targets), off, _dev(dloss))
-    onehot = np.zeros_like(zd)
-    np.put_along_axis(onehot, np.clip(tl, 0, vl - 1)[..., None], local[..., None].astype(np.float64), axis=-1)
-    want_dz = (np.exp(zd - zd.max(axis=-1, keepdims=True)) / want_s[..., None] - onehot) * dloss.double().numpy()[..., None]
-    assert m2(dz.float().cpu().numpy(), want_dz) <= TOL_BF16
-    dz_ref = torch.from_numpy(want_dz).to(torch.bfloat16)                # the oracle's stored dz on both sides
-    dzn = to_nt(dz_ref, (B, L, VOCAB))
-    dw = mtf.einsum_local(_dev(cfg["x"]), (B, L, D), _dev(dz_ref), (B, L, VOCAB), (D, VOCAB), out_dtype=torch.float32)
-    dx = mtf.einsum_local(_dev(dz_ref), (B, L, VOCAB), _dev(cfg["w_vocab"]), (D, VOCAB), (B, L, D),
+        assert m2(sumexp.cpu().numpy(), full["s"].data) <= TOL_F32
+    # backward from the oracle's group-wide statistics
+    dloss = to_nt(cfg["dloss"], (B, L))
+    ref = OV.xent_bwd(x, w_full, targets, full["logits"], full["m"], full["s"], dloss)
+    s_grp = _dev(torch.from_numpy(full["s"].data).float())
+    dz = mtf.xent_grad_local(z, m_grp, s_grp, _dev(cfg["targets"]), off, _dev(cfg["dloss"]))
+    dz_ref = slice_tensor(ref["dz"], mesh, layout, c)
+    assert m2(dz.float().cpu().numpy(), dz_ref.data) <= TOL_BF16
+    # the two gradient einsums from the oracle's stored dz (already on the bf16 grid) on both sides
+    dz_dev = _dev(torch.from_numpy(dz_ref.data).to(torch.bfloat16))
+    assert np.array_equal(dz_dev.double().cpu().numpy(), dz_ref.data)
+    dw = mtf.einsum_local(_dev(cfg["x"]), (B, L, D), dz_dev, (B, L, VOCAB), (D, VOCAB), out_dtype=torch.float32)
+    dx = mtf.einsum_local(dz_dev, (B, L, VOCAB), _dev(cfg["w_vocab"]), (D, VOCAB), (B, L, D),
                           out_dtype=torch.float32)
-    assert m2(dw.cpu().numpy(), np.einsum("bld,blv->dv", x.data, dzn.data)) <= TOL_BF16
-    assert m2(dx.cpu().numpy(), np.einsum("blv,dv->bld", dzn.data, w.data)) <= TOL_BF16
+    assert m2(dw.cpu().numpy(), slice_tensor(ref["dw"], mesh, layout, c).data) <= TOL_BF16
+    assert m2(dx.cpu().numpy(), ref["dx"].data) <= TOL_BF16
 
 
 def test_vocab_split_on_virtual_meshes(mtf):

@@ -124,6 +124,37 @@ def test_three_operands_and_linearity():
     assert np.all(ab >= np.abs(f(a)) - 1e-12)
 
 
+def test_library_path_at_mid_size_against_the_definition():
+    """The large-size path hands the contraction to numpy.einsum(optimize=True), which at these
+    extents re-orders the operands, merges dims and calls the matrix-multiply routine: the result
+    must still be the definition's, to fp64 summation-order accuracy.  Shapes of the layer's
+    einsums (a projection with a batch dim, its weight gradient with two reduced dims and a
+    transposed output, the two attention products with two batch dims), extents 48..80."""
+    rng = np.random.default_rng(11)
+    cases = [
+        ([((3, 48, 80), ("batch", "length", "d_model")), ((80, 64), ("d_model", "d_ff"))], ("batch", "length", "d_ff")),
+        ([((3, 48, 80), ("batch", "length", "d_model")), ((3, 48, 64), ("batch", "length", "d_ff"))], ("d_ff", "d_model")),
+        ([((2, 48, 3, 16), ("batch", "length", "heads", "d_k")), ((2, 56, 3, 16), ("batch", "memory_length", "heads", "d_k"))],
+         ("batch", "heads", "length", "memory_length")),
+        ([((2, 3, 48, 56), ("batch", "heads", "length", "memory_length")), ((2, 56, 3, 16), ("batch", "memory_length", "heads", "d_v"))],
+         ("batch", "length", "heads", "d_v")),
+        ([((2, 48, 3, 16), ("batch", "length", "heads", "d_v")), ((3, 16, 80), ("heads", "d_v", "d_model"))],
+         ("batch", "length", "d_model")),
+    ]
+    for operands, out in cases:
+        inputs = [nt(rng.standard_normal(shape), dims) for shape, dims in operands]
+        want, got = both_paths(inputs, out)
+        scale = einsum_abs(inputs, out).data                              # |x|.|y| of every output
+        assert got.shape == want.shape
+        assert np.max(np.abs(got - want) / scale) <= 1e-12, (operands, out)
+        # and an independent statement of the same contraction: plain loops over the batch dims
+        # around numpy's matrix product for the first case
+    a, b = rng.standard_normal((3, 48, 80)), rng.standard_normal((80, 64))
+    want = np.stack([a[i] @ b for i in range(3)])
+    for got in both_paths([nt(a, ("batch", "length", "d_model")), nt(b, ("d_model", "d_ff"))], ("batch", "length", "d_ff")):
+        np.testing.assert_allclose(got, want, rtol=1e-12, atol=1e-12)
+
+
 def test_errors():
     a = nt(np.zeros((2, 2)), ("d_model", "d_ff"))
     with pytest.raises(EinsumError) as e:
