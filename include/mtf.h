@@ -213,6 +213,21 @@ int mtf_reduce_local(const void* in, const mtf_shape* in_local, void* out,
                      const mtf_shape* out_local, mtf_dtype in_dt, mtf_dtype out_dt,
                      mtf_reduce_op op, void* workspace, size_t workspace_bytes, void* stream);
 
+/* mtf_reduce_local for callers that cannot allocate device memory or carry a workspace (code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): same arguments minus
+ * the workspace, same kernels, bit-identical results.  The scratch (the chunk partials of a
+ * column reduction) is a static device array inside the library, MTF_REDUCE_STATIC_MAX_SCRATCH
+ * bytes per GPU, held until the process ends.  The call allocates and frees nothing and does not
+ * synchronise.  A reduction whose mtf_reduce_local_workspace_bytes() exceeds the maximum is
+ * rejected with MTF_ERR_WORKSPACE (nothing launched).  All calls on one GPU share that GPU's
+ * array: calls that overlap in time on one GPU (different streams or host threads) race; calls
+ * ordered on one stream are safe (every partial a call reads it has written itself, so nothing
+ * needs clearing between calls). */
+#define MTF_REDUCE_STATIC_MAX_SCRATCH (4u << 20)
+int mtf_reduce_local_static(const void* in, const mtf_shape* in_local, void* out,
+                            const mtf_shape* out_local, mtf_dtype in_dt, mtf_dtype out_dt,
+                            mtf_reduce_op op, void* stream);
+
 /* ---------------------------------------------------------------- device: vocabulary-split operations
  * Section 'Model-Parallel "Transformer"': vocab is split across the mesh like d_ff and heads.
  * The paper gives no formulas for the operations that carry vocab; they are taken as its own

@@ -316,6 +316,26 @@ def reduce_local(x, x_dims, out_dims, op=REDUCE_SUM, out_dtype=torch.float32):
     return out
 
 
+REDUCE_STATIC_MAX_SCRATCH = 4 << 20
+
+
+def reduce_local_static(x, x_dims, out_dims, op=REDUCE_SUM, out=None, out_dtype=torch.float32):
+    """reduce_local through the entry point that allocates nothing inside the library (its scratch
+    is a static device array); `out` may be passed in so that the call allocates nothing at all."""
+    k = _Keep()
+    named = _named(x, x_dims)
+    sizes = dict(named)
+    sx = k.shape(named)
+    missing = [d for d in out_dims if d not in sizes]
+    out_shape = [(d, sizes.get(d, 1)) for d in out_dims]
+    if out is None:
+        out = torch.empty([1] if missing else [n for _, n in out_shape], dtype=out_dtype, device=x.device)
+    so = k.shape(out_shape)
+    _check(lib.mtf_reduce_local_static(_ptr(x), C.byref(sx), _ptr(out), C.byref(so), _dt(x), _dt(out), int(op),
+                                       _stream()))
+    return out
+
+
 # ------------------------------------------------------------------ vocabulary-split operations
 def embedding_local(ids, table_local, vocab_offset, out_dtype=torch.float32):
     """ids int32 [...]; table_local bf16 [vocab_local, d_model] -> partial sum [..., d_model]."""

@@ -2,6 +2,7 @@
 // reductions (section "Operation Implementation", paragraph "Reduction"), on one processor's
 // slices.  Both are HBM-bound: every element is read once.
 #include <algorithm>
+#include <mutex>
 
 #include "device_common.h"
 #include "reduce_local.h"
@@ -336,6 +337,38 @@ int reduce_cols_sum(const bf16_t* in, float* out, int64_t rows, int64_t cols, vo
 
 using namespace mtf;
 
+// ------------------------------------------------------------------------------- static scratch
+// Scratch of the entry point that allocates nothing (mtf_reduce_local_static): the chunk partials
+// of the column reduction live in a file-scope device array instead of a caller workspace.  Every
+// device the library runs on holds its own copy of the array at its own address; in host code the
+// array's NAME is only a handle for hipGetSymbolAddress, never a device address.
+static __device__ __align__(256) unsigned char scratch[MTF_REDUCE_STATIC_MAX_SCRATCH];
+
+static constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mutex;
+static void* g_scratch_ptr[kMaxDevices] = {};  // per device: address of `scratch` there (nullptr: not asked yet)
+
+// *out = device address of `scratch` on the current device (looked up once per device, with that
+// device current).  Returns MTF_OK or the error.
+static int static_scratch(void** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+  if (dev < 0 || dev >= kMaxDevices)
+    return fail(MTF_ERR_UNSUPPORTED, "device ordinal %d outside 0..%d", dev, kMaxDevices - 1);
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return hip_fail(e, "hipGetSymbolAddress(scratch)");
+    if (!ptr) return fail(MTF_ERR_HIP, "hipGetSymbolAddress(scratch) returned a null address");
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return MTF_OK;
+}
+
+
 extern "C" {
 
 int mtf_add_broadcast(const void* a, const mtf_shape* a_local, const void* b, const mtf_shape* b_local, void* out,
@@ -393,24 +426,48 @@ size_t mtf_reduce_local_workspace_bytes(const mtf_shape* in_local, const mtf_sha
   return plan_reduce(din, dout).workspace;
 }
 
-int mtf_reduce_local(const void* in, const mtf_shape* in_local, void* out, const mtf_shape* out_local,
-                     mtf_dtype in_dt, mtf_dtype out_dt, mtf_reduce_op op, void* workspace, size_t workspace_bytes,
-                     void* stream) {
+// Shared body of mtf_reduce_local and mtf_reduce_local_static.  use_static: the chunk partials go
+// to the library's static device array instead of `workspace`.
+static int reduce_local_impl(const void* in, const mtf_shape* in_local, void* out, const mtf_shape* out_local,
+                             mtf_dtype in_dt, mtf_dtype out_dt, mtf_reduce_op op, bool use_static, void* workspace,
+                             size_t workspace_bytes, void* stream) {
   Dims din, dout;
   if (int rc = check_reduce_shapes(in_local, out_local, &din, &dout)) return rc;
   if (!in || !out) return fail(MTF_ERR_NULL, "in / out");
   if ((in_dt != MTF_F32 && in_dt != MTF_BF16) || (out_dt != MTF_F32 && out_dt != MTF_BF16))
     return fail(MTF_ERR_UNSUPPORTED, "dtype");
   if (op != MTF_REDUCE_SUM && op != MTF_REDUCE_MAX) return fail(MTF_ERR_UNSUPPORTED, "reduction %d", (int)op);
-  if (!aligned16(in) || !aligned16(out) || !aligned16(workspace)) return fail(MTF_ERR_ALIGN, "in / out / workspace");
+  if (!aligned16(in) || !aligned16(out) || (!use_static && !aligned16(workspace)))
+    return fail(MTF_ERR_ALIGN, "in / out / workspace");
   const ReducePlan p = plan_reduce(din, dout);
-  if (p.workspace > 0 && (!workspace || workspace_bytes < p.workspace))
+  if (use_static) {
+    if (p.workspace > (size_t)MTF_REDUCE_STATIC_MAX_SCRATCH)
+      return fail(MTF_ERR_WORKSPACE,
+                  "mtf_reduce_local_static: this reduction needs %zu bytes of scratch, the static buffer holds %zu; "
+                  "use mtf_reduce_local with a workspace",
+                  p.workspace, (size_t)MTF_REDUCE_STATIC_MAX_SCRATCH);
+    workspace = nullptr;
+    if (p.workspace > 0)
+      if (int rc = static_scratch(&workspace)) return rc;
+  } else if (p.workspace > 0 && (!workspace || workspace_bytes < p.workspace)) {
     return fail(MTF_ERR_WORKSPACE, "mtf_reduce_local needs %zu bytes", p.workspace);
+  }
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (in_dt == MTF_F32 && out_dt == MTF_F32) return run_reduce_op<float, float>(op, in, din, out, dout, p, workspace, s);
   if (in_dt == MTF_F32) return run_reduce_op<float, bf16_t>(op, in, din, out, dout, p, workspace, s);
   if (out_dt == MTF_F32) return run_reduce_op<bf16_t, float>(op, in, din, out, dout, p, workspace, s);
   return run_reduce_op<bf16_t, bf16_t>(op, in, din, out, dout, p, workspace, s);
+}
+
+int mtf_reduce_local(const void* in, const mtf_shape* in_local, void* out, const mtf_shape* out_local,
+                     mtf_dtype in_dt, mtf_dtype out_dt, mtf_reduce_op op, void* workspace, size_t workspace_bytes,
+                     void* stream) {
+  return reduce_local_impl(in, in_local, out, out_local, in_dt, out_dt, op, false, workspace, workspace_bytes, stream);
+}
+
+int mtf_reduce_local_static(const void* in, const mtf_shape* in_local, void* out, const mtf_shape* out_local,
+                            mtf_dtype in_dt, mtf_dtype out_dt, mtf_reduce_op op, void* stream) {
+  return reduce_local_impl(in, in_local, out, out_local, in_dt, out_dt, op, true, nullptr, 0, stream);
 }
 
 }  // extern "C"
