@@ -111,8 +111,9 @@ def main():
                 mtf.ffn_bias_bwd(g["x"], a, g["w_in"], g["w_out"], g["dy"], workspace=ws)
     elif args.workload == "mesh":
         # config 4: the feed-forward sublayer on a VIRTUAL 4x4 mesh held on this one GPU (batch over
-        # rows, d_ff over cols): 16 processors' local einsums, then the partial sums "summed up by
-        # processor-column" - 4 groups of 4 - by the reduce kernel that stands in for the Allreduce
+        # rows, d_ff over cols): 16 processors' local einsums, then the partial sums added up within
+        # each mesh row (over the column index) - 4 groups of 4 - by the reduce kernel that stands
+        # in for the Allreduce (section "Data-Parallel, Model-Parallel Layouts")
         cfg = mtf_inputs.config4()
         mesh, layout = cfg["mesh"], cfg["layout"]
         B, L, D = cfg["x"].shape

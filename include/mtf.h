@@ -21,8 +21,9 @@
  *     through `workspace` arguments sized by the mtf_*_workspace_bytes() calls.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Device calls
  *     are asynchronous on it; the library never synchronises.
- *   - Host-only calls (mtf_slice, mtf_einsum_plan, mtf_reshape_plan, rank/coord helpers,
- *     *_workspace_bytes, mtf_status_string) touch no GPU and work on a machine without one.
+ *   - Host-only calls (mtf_slice, mtf_einsum_plan, mtf_einsum_local_path, mtf_reshape_plan,
+ *     rank/coord helpers, *_workspace_bytes, mtf_status_string) touch no GPU and work on a
+ *     machine without one.
  *
  * Contents: slices and lowering plans (host); slice gather, the local einsum with its fused
  * epilogues, partial-sum reduce (the Allreduce stand-in on a virtual mesh); component-wise
@@ -140,8 +141,9 @@ int mtf_einsum_plan(const mtf_shape* a, const mtf_shape* b, const mtf_shape* out
 
 /* ---------------------------------------------------------------- device: slice gather / scatter
  * Copies the slice mtf_slice() describes between a full tensor and a contiguous slice buffer
- * (scatter = 0: slice <- full;  scatter != 0: full <- slice).  full, slice: device.  Bit-exact. */
-int mtf_slice_copy(const void* full, void* slice, const mtf_shape* t, const mtf_place* p,
+ * (scatter = 0: slice <- full, `full` is only read;  scatter != 0: full <- slice, `slice` is only
+ * read).  full, slice: device.  Bit-exact. */
+int mtf_slice_copy(void* full, void* slice, const mtf_shape* t, const mtf_place* p,
                    mtf_dtype dt, int scatter, void* stream);
 
 /* ---------------------------------------------------------------- device: the local einsum
@@ -157,10 +159,26 @@ int mtf_einsum_local(const void* a, const mtf_shape* a_local, const void* b,
                      mtf_dtype in_dt, mtf_dtype out_dt, mtf_epilogue epi, const void* aux,
                      float alpha, int accumulate, void* stream);
 
+/* Which kernel mtf_einsum_local would run for exactly these arguments: MTF_PATH_MFMA (the bf16
+ * matrix-core kernel) or MTF_PATH_GENERIC (one thread per output element, fp32 FMA: the same
+ * result up to summation order, one to two orders of magnitude slower at layer sizes), or the
+ * negative status mtf_einsum_local would return.  The generic kernel takes over for fp32 inputs,
+ * one-operand einsums, dim structures that do not fold to a (batched) matrix product, extents or
+ * leading dims not divisible by 8 (odd leading dims), leading dims too large for the kernel's
+ * 32-bit offsets, and a bias over an output dim that was merged with its neighbour.  Host only:
+ * looks at shapes and addresses, launches nothing, needs no GPU. */
+#define MTF_PATH_GENERIC 0
+#define MTF_PATH_MFMA 1
+int mtf_einsum_local_path(const void* a, const mtf_shape* a_local, const void* b,
+                          const mtf_shape* b_local, void* out, const mtf_shape* out_local,
+                          mtf_dtype in_dt, mtf_dtype out_dt, mtf_epilogue epi, const void* aux,
+                          float alpha, int accumulate);
+
 /* ---------------------------------------------------------------- device: partial-sum reduce
  * out[i] = (residual ? residual[i] : 0) + partials[0][i] + ... + partials[n-1][i], summed in
  * fp32 in that fixed order.  Stands in, on one GPU, for the Allreduce over one group of a
- * virtual mesh ("summed up by processor-column" in the 2-D layout of the worked example).
+ * virtual mesh (the per-column sums of the 2-D layout of the worked example, section
+ * "Data-Parallel, Model-Parallel Layouts").
  * partials: HOST array of n (1..64) DEVICE pointers to fp32 buffers of `count` elements. */
 int mtf_reduce_partials(const void* const* partials, int32_t n, const void* residual,
                         mtf_dtype residual_dt, void* out, mtf_dtype out_dt, int64_t count,

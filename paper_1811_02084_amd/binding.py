@@ -274,6 +274,27 @@ def einsum_local(a, a_dims, b, b_dims, out_dims, out_dtype=None, epi=EPI_NONE, a
     return out
 
 
+PATH_GENERIC, PATH_MFMA = 0, 1
+
+
+def einsum_local_path(a_dims, b_dims, out_dims, in_dtype=torch.bfloat16, out_dtype=torch.float32, epi=EPI_NONE,
+                      a_ptr=0x1000, b_ptr=0x2000, out_ptr=0x3000, aux_ptr=0x4000):
+    """Which kernel einsum_local would run (PATH_MFMA / PATH_GENERIC) for operands of these named
+    shapes ([(name, size)] lists) and addresses.  Host only: nothing is dereferenced or launched."""
+    k = _Keep()
+    sa, so = k.shape(a_dims), k.shape(out_dims)
+    sb = k.shape(b_dims) if b_dims is not None else None
+    code = lambda dt: F32 if dt == torch.float32 else BF16
+    needs_aux = epi in (EPI_MASK_GT0, EPI_BIAS, EPI_BIAS_RELU)
+    rc = lib.mtf_einsum_local_path(C.c_void_p(a_ptr), C.byref(sa), C.c_void_p(b_ptr) if sb is not None else None,
+                                   C.byref(sb) if sb is not None else None, C.c_void_p(out_ptr), C.byref(so),
+                                   code(in_dtype), code(out_dtype), int(epi),
+                                   C.c_void_p(aux_ptr) if needs_aux else None, C.c_float(1.0), 0)
+    if rc < 0:
+        raise MtfError(rc)
+    return rc
+
+
 def reduce_partials(partials, residual=None, out_dtype=torch.float32, out=None):
     n = len(partials)
     count = partials[0].numel()

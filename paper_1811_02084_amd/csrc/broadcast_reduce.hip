@@ -45,7 +45,7 @@ __global__ void __launch_bounds__(256) add_broadcast_kernel(const InT* __restric
       ib += (rem % g.extent[d]) * g.b_stride[d];
       rem /= g.extent[d];
     }
-    const int64_t step = g.b_stride[g.rank - 1];
+    const int64_t step = g.rank > 0 ? g.b_stride[g.rank - 1] : 0;  // rank 0: one element
     for (int e = 0; e < vec; ++e) st<OutT>(out, first + e, ld<InT>(a, first + e) + ld<InT>(b, ib + e * step));
   }
 }

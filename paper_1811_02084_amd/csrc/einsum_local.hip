@@ -208,18 +208,26 @@ bool as_gemm(const Canon& c, GemmDesc* d, bool* swapped) {
 
 using namespace mtf;
 
-extern "C" int mtf_einsum_local(const void* a, const mtf_shape* a_local, const void* b,
-                                const mtf_shape* b_local, void* out, const mtf_shape* out_local,
-                                mtf_dtype in_dt, mtf_dtype out_dt, mtf_epilogue epi,
-                                const void* aux, float alpha, int accumulate, void* stream) {
+namespace {
+
+// Validation and kernel choice shared by mtf_einsum_local and mtf_einsum_local_path.
+struct EinsumRoute {
   Dims da, db, dout;
-  if (int rc = load_shape(a_local, "a", &da)) return rc;
-  const bool has_b = b != nullptr || b_local != nullptr;
-  if (has_b) {
+  bool has_b = false;
+  bool use_gemm = false;
+  GemmDesc gemm;
+};
+
+int route_einsum(const void* a, const mtf_shape* a_local, const void* b, const mtf_shape* b_local, void* out,
+                 const mtf_shape* out_local, mtf_dtype in_dt, mtf_dtype out_dt, mtf_epilogue epi, const void* aux,
+                 float alpha, int accumulate, EinsumRoute* r) {
+  if (int rc = load_shape(a_local, "a", &r->da)) return rc;
+  r->has_b = b != nullptr || b_local != nullptr;
+  if (r->has_b) {
     if (!b || !b_local) return fail(MTF_ERR_NULL, "b given without its shape (or the reverse)");
-    if (int rc = load_shape(b_local, "b", &db)) return rc;
+    if (int rc = load_shape(b_local, "b", &r->db)) return rc;
   }
-  if (int rc = load_shape(out_local, "output", &dout)) return rc;
+  if (int rc = load_shape(out_local, "output", &r->dout)) return rc;
   if (!a || !out) return fail(MTF_ERR_NULL, "a / out");
   if ((in_dt != MTF_F32 && in_dt != MTF_BF16) || (out_dt != MTF_F32 && out_dt != MTF_BF16))
     return fail(MTF_ERR_UNSUPPORTED, "dtype");
@@ -230,10 +238,9 @@ extern "C" int mtf_einsum_local(const void* a, const mtf_shape* a_local, const v
   if (!aligned16(a) || !aligned16(b) || !aligned16(out) || !aligned16(aux))
     return fail(MTF_ERR_ALIGN, "a / b / out / aux");
   Canon c;
-  if (int rc = canonicalize(da, has_b ? &db : nullptr, dout, &c)) return rc;
-  hipStream_t s = static_cast<hipStream_t>(stream);
-  if (in_dt == MTF_BF16 && has_b) {
-    GemmDesc d;
+  if (int rc = canonicalize(r->da, r->has_b ? &r->db : nullptr, r->dout, &c)) return rc;
+  if (in_dt == MTF_BF16 && r->has_b) {
+    GemmDesc& d = r->gemm;
     bool swapped = false;
     if (as_gemm(c, &d, &swapped)) {  // exchanges the operands when OUT has A's dims innermost
       d.A[0] = static_cast<const bf16_t*>(swapped ? b : a);
@@ -245,12 +252,36 @@ extern "C" int mtf_einsum_local(const void* a, const mtf_shape* a_local, const v
       // the bias runs over OUT's innermost dim: a plain n-vector unless that dim was merged
       // with the one before it
       d.bias = with_bias ? static_cast<const bf16_t*>(aux) : nullptr;
-      const bool bias_ok = !with_bias || (dout.rank > 0 && d.N == dout.size[dout.rank - 1]);
+      const bool bias_ok = !with_bias || (r->dout.rank > 0 && d.N == r->dout.size[r->dout.rank - 1]);
       d.alpha = alpha;
       d.accumulate = accumulate != 0;
-      if (bias_ok && gemm_bf16_supported(d)) return gemm_bf16_launch(d, s);
+      r->use_gemm = bias_ok && gemm_bf16_supported(d);
     }
   }
-  return launch_generic(a, da, has_b ? b : nullptr, has_b ? &db : nullptr, out, dout, in_dt, out_dt,
+  return MTF_OK;
+}
+
+}  // namespace
+
+extern "C" int mtf_einsum_local(const void* a, const mtf_shape* a_local, const void* b,
+                                const mtf_shape* b_local, void* out, const mtf_shape* out_local,
+                                mtf_dtype in_dt, mtf_dtype out_dt, mtf_epilogue epi,
+                                const void* aux, float alpha, int accumulate, void* stream) {
+  EinsumRoute r;
+  if (int rc = route_einsum(a, a_local, b, b_local, out, out_local, in_dt, out_dt, epi, aux, alpha, accumulate, &r))
+    return rc;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (r.use_gemm) return gemm_bf16_launch(r.gemm, s);
+  return launch_generic(a, r.da, r.has_b ? b : nullptr, r.has_b ? &r.db : nullptr, out, r.dout, in_dt, out_dt,
                         epi, aux, alpha, accumulate, s);
+}
+
+extern "C" int mtf_einsum_local_path(const void* a, const mtf_shape* a_local, const void* b,
+                                     const mtf_shape* b_local, void* out, const mtf_shape* out_local,
+                                     mtf_dtype in_dt, mtf_dtype out_dt, mtf_epilogue epi,
+                                     const void* aux, float alpha, int accumulate) {
+  EinsumRoute r;
+  if (int rc = route_einsum(a, a_local, b, b_local, out, out_local, in_dt, out_dt, epi, aux, alpha, accumulate, &r))
+    return rc;
+  return r.use_gemm ? MTF_PATH_MFMA : MTF_PATH_GENERIC;
 }

@@ -158,7 +158,7 @@ using namespace mtf;
 
 extern "C" {
 
-int mtf_slice_copy(const void* full, void* slice, const mtf_shape* t, const mtf_place* p,
+int mtf_slice_copy(void* full, void* slice, const mtf_shape* t, const mtf_place* p,
                    mtf_dtype dt, int scatter, void* stream) {
   Dims d;
   if (int rc = load_shape(t, "tensor", &d)) return rc;

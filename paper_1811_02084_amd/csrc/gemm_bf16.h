@@ -8,7 +8,6 @@ namespace mtf {
 
 constexpr int kMaxSegments = 3;
 constexpr int kMaxGroup = 4;
-constexpr int kLargeTileMinCount = 192;  // fewer 256x256 tiles than this: use 128x128 tiles
 
 // C[z][m][n] (+)= alpha * sum_s sum_k A_s[z][m][k] * B_s[z][k][n], then the epilogue.
 //
@@ -52,12 +51,11 @@ struct GemmDesc {
   int nextra = 0;
   Extra extra[kMaxGroup - 1];
   int tile = 0;  // 0 = choose by output size, 1 = 128x128 tiles, 2 = 256x256 tiles, 3 = 128x128 with 4 stages
-  // tuning aid: if set, workgroup 0 stores {shader-clock ticks, 100 MHz ticks} spent in the kernel
-  uint64_t* debug_clocks = nullptr;
 };
 
-// True when the MFMA kernel can run this problem (alignment and divisibility of the leading
-// dims by 8 elements); otherwise the caller must use the generic kernel.
+// True when the MFMA kernel can run this problem (alignment, divisibility of the leading dims by
+// 8 elements, leading dims small enough for the kernel's 32-bit per-lane byte offsets); otherwise
+// the caller must use the generic kernel.  Looks at sizes and addresses only (no GPU needed).
 bool gemm_bf16_supported(const GemmDesc& d);
 
 // Enqueues the GEMM on `stream`.  Returns MTF_OK or an error code (nothing launched on error).

@@ -1,6 +1,6 @@
 // bf16 x bf16 -> fp32-accumulate GEMM on the gfx950 matrix cores, with fused component-wise
-// epilogues.  Every contraction of the Transformer-layer path lowers to this kernel (the paper's
-// "computation time is dominated by that of einsum operations").
+// epilogues.  Every contraction of the Transformer-layer path lowers to this kernel (section
+// "Performance Comparison": the einsums are where the computation time goes).
 //
 // Design (MI355X):
 //   * large tile: one workgroup = 8 wavefronts (2 per SIMD) computes 256x256 of C, K advanced 64
@@ -85,7 +85,6 @@ struct GemmArgs {
   int tiles_m[kMaxGroup], tiles_n[kMaxGroup];
   int batch1;
   int64_t sA0, sA1, sB0, sB1, sC0, sC1;
-  uint64_t* debug_clocks;
 };
 
 // Direct global -> LDS load of 16 bytes per lane: lane i's bytes land at lds_addr + 16*i.
@@ -198,7 +197,6 @@ __global__ void __launch_bounds__(Cfg::kThreads, Cfg::kWavesPerSimd) gemm_bf16_k
   constexpr int NS = Cfg::kStages;
   __shared__ __attribute__((aligned(1024))) char ring[NS * Cfg::kStage];
 
-  const uint64_t t_start = g.debug_clocks ? clock64() : 0, w_start = g.debug_clocks ? wall_clock64() : 0;
   // ---- which tile: XCD-aware remap, then patches of kGroupM tile rows
   const int grp = g.ngroup > 1 ? blockIdx.y : 0;  // grouped launch: blockIdx.y picks the problem
   const int M = g.M[grp], N = g.N[grp], tiles_m = g.tiles_m[grp], tiles_n = g.tiles_n[grp];
@@ -376,10 +374,6 @@ __global__ void __launch_bounds__(Cfg::kThreads, Cfg::kWavesPerSimd) gemm_bf16_k
     compute(std::false_type{}, total_tiles - 1, ring + stage * Cfg::kStage, nullptr, nullptr);
   }
 
-  if (g.debug_clocks && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) {
-    g.debug_clocks[0] = clock64() - t_start;
-    g.debug_clocks[1] = wall_clock64() - w_start;
-  }
   // ---- epilogue.  A lane holds, per accumulator, one row m and 4 x 4 consecutive n: stored
   // directly that would be 16-byte pieces scattered over 32 rows per instruction.  Instead each
   // wave passes its 32 x 64 accumulator slabs through a private LDS area (the operand ring is
@@ -462,11 +456,6 @@ __global__ void __launch_bounds__(Cfg::kThreads, Cfg::kWavesPerSimd) gemm_bf16_k
     }
     __builtin_amdgcn_wave_barrier();
   }
-  if (g.debug_clocks && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) {
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // stores issued by this wave have been accepted
-    g.debug_clocks[2] = clock64() - t_start;
-    g.debug_clocks[3] = wall_clock64() - w_start;
-  }
 }
 
 template <class Cfg, bool A_K, bool B_K, int EPI, bool OUT_BF16>
@@ -528,8 +517,20 @@ int launch_cfg(const GemmDesc& d, const GemmArgs& a, int batch, hipStream_t s) {
 
 }  // namespace
 
+// The tile loaders keep per-lane byte offsets relative to the tile origin in 32 bits: up to
+// (tile rows - 1) * ld * 2 + 128 for a k-contiguous operand (256-row tile) and 63 * ld * 2 +
+// 2 * tile columns for an mn-contiguous one.  Leading dims beyond this would wrap.
+static bool ld_fits_32bit_offsets(int64_t ld, bool kcontig) {
+  const int64_t worst = kcontig ? 255 * ld * 2 + 128 : 63 * ld * 2 + 512;
+  return ld >= 0 && ld < (INT64_C(1) << 40) && worst <= (int64_t)UINT32_MAX;
+}
+
 bool gemm_bf16_supported(const GemmDesc& d) {
   if (d.nseg < 1 || d.nseg > kMaxSegments) return false;
+  if (!ld_fits_32bit_offsets(d.lda, d.a_kcontig) || !ld_fits_32bit_offsets(d.ldb, d.b_kcontig)) return false;
+  for (int p = 0; p < d.nextra && p < kMaxGroup - 1; ++p)
+    if (!ld_fits_32bit_offsets(d.extra[p].lda, d.a_kcontig) || !ld_fits_32bit_offsets(d.extra[p].ldb, d.b_kcontig))
+      return false;
   if (d.M <= 0 || d.N <= 0 || d.M > INT32_MAX || d.N > INT32_MAX) return false;
   if (d.lda % 8 || d.ldb % 8 || d.ldc % 4 || d.N % 8) return false;
   if (!d.a_kcontig && d.M % 8) return false;
@@ -585,7 +586,6 @@ int gemm_bf16_launch(const GemmDesc& d, hipStream_t stream) {
   a.alpha = d.alpha;
   a.accumulate = d.accumulate ? 1 : 0;
   a.batch1 = (int)d.batch1;
-  a.debug_clocks = d.debug_clocks;
   a.sA0 = d.sA0; a.sA1 = d.sA1; a.sB0 = d.sB0; a.sB1 = d.sB1; a.sC0 = d.sC0; a.sC1 = d.sC1;
   const int batch = (int)(d.batch0 * d.batch1);
   // Tile choice: the large tile moves half the bytes per flop, but needs enough tiles to occupy

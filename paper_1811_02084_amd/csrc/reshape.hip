@@ -94,6 +94,8 @@ extern "C" int mtf_reshape_virtual(const void* const* in_slices, const mtf_shape
   if (processors > kMaxProcessors)
     return fail(MTF_ERR_UNSUPPORTED, "virtual reshape over %lld processors (at most %d)", (long long)processors,
                 kMaxProcessors);
+  // a rank-0 tensor has no dim to rename or split (and no innermost position for the copy kernel)
+  if (r.rank == 0) return fail(MTF_ERR_RANK, "reshape of a rank-0 tensor");
   ReshapeArgs g{};
   for (int64_t q = 0; q < processors; ++q) {
     if (!in_slices[q]) return fail(MTF_ERR_NULL, "in_slices[%lld]", (long long)q);

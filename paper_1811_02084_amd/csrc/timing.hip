@@ -3,8 +3,7 @@
 // totals.  Used by the benchmark to time the dominant kernel inside the timed region.
 #include "timing.h"
 
-#include <cstdio>
-#include <cstdlib>
+#include <atomic>
 #include <cstring>
 #include <mutex>
 #include <vector>
@@ -21,7 +20,7 @@ struct Record {
 };
 
 std::mutex g_mu;
-bool g_enabled = false;
+std::atomic<bool> g_enabled{false};  // read without the mutex on every launch
 std::vector<Record> g_records;
 std::vector<hipEvent_t> g_free_events;
 
@@ -40,8 +39,9 @@ hipEvent_t take_event() {
 
 LaunchTimer::LaunchTimer(const char* kind, double flops, double bytes, hipStream_t stream)
     : slot_(-1), stream_(stream) {
+  if (!g_enabled.load(std::memory_order_relaxed)) return;  // timing off: no lock, no event
   std::lock_guard<std::mutex> lock(g_mu);
-  if (!g_enabled) return;
+  if (!g_enabled.load(std::memory_order_relaxed)) return;
   Record r{kind, flops, bytes, take_event(), take_event()};
   if (!r.start || !r.stop) return;
   (void)hipEventRecord(r.start, stream);
@@ -121,7 +121,7 @@ int mtf_mfma_ceiling(const void* operands, int32_t iters, void* sink, double* fl
 
 int mtf_timing_enable(int on) {
   std::lock_guard<std::mutex> lock(g_mu);
-  g_enabled = on != 0;
+  g_enabled.store(on != 0, std::memory_order_relaxed);
   return MTF_OK;
 }
 
@@ -130,10 +130,6 @@ int mtf_timing_collect(mtf_kernel_time* out, int32_t max_kinds, int32_t* n_kinds
   std::lock_guard<std::mutex> lock(g_mu);
   int n = 0;
   int rc = MTF_OK;
-  // tuning aid: MTF_TIMING_TRACE=1 lists every launch in issue order on stderr
-  const char* trace_env = std::getenv("MTF_TIMING_TRACE");
-  const bool trace = trace_env && trace_env[0] == '1';
-  int seq = 0;
   for (Record& r : g_records) {
     float ms = 0.f;
     hipError_t e = hipEventSynchronize(r.stop);
@@ -142,9 +138,6 @@ int mtf_timing_collect(mtf_kernel_time* out, int32_t max_kinds, int32_t* n_kinds
     g_free_events.push_back(r.start);
     g_free_events.push_back(r.stop);
     if (e != hipSuccess) continue;
-    if (trace)
-      std::fprintf(stderr, "[mtf timing] %4d %8.2f us %8.1f TFLOP/s %8.1f GB/s  %s\n", seq++, ms * 1e3,
-                   r.flops / ms * 1e-9, r.bytes / ms * 1e-6, r.kind);
     int k = 0;
     while (k < n && std::strcmp(out[k].kernel, r.kind) != 0) ++k;
     if (k == n) {

@@ -227,6 +227,7 @@ int mtf_xent_stats_local(const void* logits_local, int64_t rows, int64_t vocab_l
   if (rows < 0 || vocab_local <= 0 || vocab_offset < 0) return fail(MTF_ERR_SIZE_MISMATCH, "loss sizes");
   if (rows == 0) return MTF_OK;
   if (!logits_local || !row_max || !targets || !sumexp || !picked) return fail(MTF_ERR_NULL, "loss buffers");
+  if (!aligned16(logits_local)) return fail(MTF_ERR_ALIGN, "logits_local");  // 16-byte row loads
   hipStream_t s = static_cast<hipStream_t>(stream);
   LaunchTimer timer("xent_stats_kernel", 0, 4.0 * rows * vocab_local + 16.0 * rows, s);
   xent_stats_kernel<<<(unsigned)ceil_div(rows, 4), 256, 0, s>>>((const float*)logits_local, (const float*)row_max,

@@ -198,3 +198,48 @@ def test_reshape_plan_matches_oracle_and_the_papers_three_cases():
                 assert got.value.name == "MTF_ERR_" + e.code, (a, b)
                 continue
             assert mtf.reshape_plan(shp(a), shp(b), two, lay2) == want, (a, b)
+
+
+def test_einsum_local_path_reports_the_kernel_that_would_run():
+    """Host-only query: which of the two kernels a local einsum would get.  Includes the bound on
+    the leading dims that the matrix-core kernel's 32-bit per-lane byte offsets impose."""
+    import torch
+    P = mtf.einsum_local_path
+    X, W, Hd = ("batch", "length", "d_model"), ("d_model", "d_ff"), ("batch", "length", "d_ff")
+    shp = lambda dims, sizes: list(zip(dims, sizes))
+    # the feed-forward einsum of config 2: bf16, everything divisible by 8
+    assert P(shp(X, (16, 256, 1024)), shp(W, (1024, 4096)), shp(Hd, (16, 256, 4096))) == mtf.PATH_MFMA
+    # its weight gradient (both operands token-major) and the transposed-weight product
+    assert P(shp(X, (16, 256, 1024)), shp(Hd, (16, 256, 4096)), shp(W, (1024, 4096))) == mtf.PATH_MFMA
+    assert P(shp(Hd, (16, 256, 4096)), shp(W, (1024, 4096)), shp(X, (16, 256, 1024))) == mtf.PATH_MFMA
+    # fp32 inputs, an odd contraction size, a one-operand einsum: the generic kernel
+    assert P(shp(X, (2, 8, 16)), shp(W, (16, 64)), shp(Hd, (2, 8, 64)), in_dtype=torch.float32) == mtf.PATH_GENERIC
+    assert P(shp(X, (2, 8, 20)), shp(W, (20, 64)), shp(Hd, (2, 8, 64))) == mtf.PATH_GENERIC
+    assert P(shp(X, (2, 8, 16)), None, [("d_model", 16)]) == mtf.PATH_GENERIC
+    # misaligned operand address: reported as the error the einsum itself would give
+    with pytest.raises(mtf.MtfError) as e:
+        P(shp(X, (2, 8, 16)), shp(W, (16, 64)), shp(Hd, (2, 8, 64)), a_ptr=0x1004)
+    assert e.value.name == "MTF_ERR_ALIGN"
+    # leading dims: a k-contiguous operand's per-lane offset reaches 255 * ld * 2 + 128 bytes, an
+    # mn-contiguous one's 63 * ld * 2 + 512; both must fit in 32 bits
+    k_ok = ((2 ** 32 - 1 - 128) // (255 * 2)) // 8 * 8            # largest ld (multiple of 8) that fits
+    assert P([("length", 8), ("d_model", k_ok)], [("d_model", k_ok), ("d_ff", 8)],
+             [("length", 8), ("d_ff", 8)]) == mtf.PATH_MFMA
+    assert P([("length", 8), ("d_model", k_ok + 8)], [("d_model", k_ok + 8), ("d_ff", 8)],
+             [("length", 8), ("d_ff", 8)]) == mtf.PATH_GENERIC
+    n_ok = ((2 ** 32 - 1 - 512) // (63 * 2)) // 8 * 8
+    assert P([("length", 8), ("d_model", 64)], [("d_model", 64), ("d_ff", n_ok)],
+             [("length", 8), ("d_ff", n_ok)]) == mtf.PATH_MFMA
+    assert P([("length", 8), ("d_model", 64)], [("d_model", 64), ("d_ff", n_ok + 8)],
+             [("length", 8), ("d_ff", n_ok + 8)]) == mtf.PATH_GENERIC
+
+
+def test_reshape_of_a_rank_0_tensor_is_refused():
+    from paper_1811_02084_amd import binding
+    k = binding._Keep()
+    empty = k.shape([])
+    place = k.place([("all", 2)], [], [0])
+    ptrs = (C.c_void_p * 2)(0x1000, 0x2000)
+    rc = binding.lib.mtf_reshape_virtual(ptrs, C.byref(empty), C.byref(empty), C.byref(place), C.c_void_p(0x3000),
+                                         0, None)
+    assert mtf.status_string(rc) == "MTF_ERR_RANK"
