@@ -8,7 +8,8 @@ CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(HERE, "libmtf.so")
 
-SOURCES = ["mtf_host.cpp", "elementwise.hip", "einsum_local.hip", "gemm_bf16.hip",
+SOURCES = ["mtf_host.cpp", "elementwise.hip", "einsum_local.hip", "gemm_bf16.hip", "gemm_bf16_large.hip", "gemm_bf16_small.hip", "gemm_bf16_small_deep.hip",
+           "gemm_bf16_split.hip",
            "attention.hip", "attention_unfused.hip", "layer.hip", "timing.hip", "broadcast_reduce.hip", "vocab.hip", "reshape.hip"]
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wno-inline-asm",

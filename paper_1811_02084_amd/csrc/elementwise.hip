@@ -1,4 +1,6 @@
 // HBM-bound helpers: slice gather/scatter, partial-sum reduce, dtype cast.
+#include <type_traits>
+
 #include "device_common.h"
 #include "timing.h"
 
@@ -95,7 +97,9 @@ struct PartialPtrs {
   const float* p[64];
 };
 
-template <bool RES_BF16, bool OUT_BF16>
+// NFIX > 0: exactly NFIX partials, their loads unrolled so that all of a thread's requests are in
+// flight before the first addition; NFIX == 0: any n, one partial at a time.
+template <bool RES_BF16, bool OUT_BF16, int NFIX>
 __global__ void __launch_bounds__(256) reduce_partials_kernel(PartialPtrs parts, int n,
                                                              const void* __restrict__ residual,
                                                              void* __restrict__ out, int64_t count) {
@@ -103,6 +107,11 @@ __global__ void __launch_bounds__(256) reduce_partials_kernel(PartialPtrs parts,
   for (int64_t v = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; v < vecs;
        v += (int64_t)gridDim.x * blockDim.x) {
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    float4 x[NFIX > 0 ? NFIX : 1];
+    if (NFIX > 0) {
+#pragma unroll
+      for (int i = 0; i < NFIX; ++i) x[i] = reinterpret_cast<const float4*>(parts.p[i])[v];
+    }
     if (residual) {
       if (RES_BF16) {
         uint2 r = reinterpret_cast<const uint2*>(residual)[v];
@@ -112,12 +121,23 @@ __global__ void __launch_bounds__(256) reduce_partials_kernel(PartialPtrs parts,
         acc = reinterpret_cast<const float4*>(residual)[v];
       }
     }
-    for (int i = 0; i < n; ++i) {  // fixed order: residual, then partial 0, 1, ...
-      float4 x = reinterpret_cast<const float4*>(parts.p[i])[v];
-      acc.x += x.x;
-      acc.y += x.y;
-      acc.z += x.z;
-      acc.w += x.w;
+    // fixed order: residual, then partial 0, 1, ...
+    if (NFIX > 0) {
+#pragma unroll
+      for (int i = 0; i < NFIX; ++i) {
+        acc.x += x[i].x;
+        acc.y += x[i].y;
+        acc.z += x[i].z;
+        acc.w += x[i].w;
+      }
+    } else {
+      for (int i = 0; i < n; ++i) {
+        const float4 y = reinterpret_cast<const float4*>(parts.p[i])[v];
+        acc.x += y.x;
+        acc.y += y.y;
+        acc.z += y.z;
+        acc.w += y.w;
+      }
     }
     if (OUT_BF16)
       reinterpret_cast<uint2*>(out)[v] = make_uint2(pack_bf16x2(acc.x, acc.y), pack_bf16x2(acc.z, acc.w));
@@ -191,14 +211,25 @@ int mtf_reduce_partials(const void* const* partials, int32_t n, const void* resi
   bool rb = residual && residual_dt == MTF_BF16, ob = out_dt == MTF_BF16;
   LaunchTimer timer("reduce_partials_kernel", 0,
                     (double)count * (4.0 * n + (residual ? (rb ? 2 : 4) : 0) + (ob ? 2 : 4)), s);
+  // one vector per thread (count / 4 threads) up to 8 workgroups per CU, grid-stride beyond
+  auto launch = [&](auto res_bf16, auto out_bf16) {
+    constexpr bool RB = decltype(res_bf16)::value, OB = decltype(out_bf16)::value;
+    switch (n) {
+      case 1: reduce_partials_kernel<RB, OB, 1><<<blocks, 256, 0, s>>>(pp, n, residual, out, count); break;
+      case 2: reduce_partials_kernel<RB, OB, 2><<<blocks, 256, 0, s>>>(pp, n, residual, out, count); break;
+      case 3: reduce_partials_kernel<RB, OB, 3><<<blocks, 256, 0, s>>>(pp, n, residual, out, count); break;
+      case 4: reduce_partials_kernel<RB, OB, 4><<<blocks, 256, 0, s>>>(pp, n, residual, out, count); break;
+      default: reduce_partials_kernel<RB, OB, 0><<<blocks, 256, 0, s>>>(pp, n, residual, out, count); break;
+    }
+  };
   if (rb && ob)
-    reduce_partials_kernel<true, true><<<blocks, 256, 0, s>>>(pp, n, residual, out, count);
+    launch(std::true_type{}, std::true_type{});
   else if (rb)
-    reduce_partials_kernel<true, false><<<blocks, 256, 0, s>>>(pp, n, residual, out, count);
+    launch(std::true_type{}, std::false_type{});
   else if (ob)
-    reduce_partials_kernel<false, true><<<blocks, 256, 0, s>>>(pp, n, residual, out, count);
+    launch(std::false_type{}, std::true_type{});
   else
-    reduce_partials_kernel<false, false><<<blocks, 256, 0, s>>>(pp, n, residual, out, count);
+    launch(std::false_type{}, std::false_type{});
   return launch_status("reduce_partials_kernel");
 }
 

@@ -1,0 +1,10 @@
+// Instantiations of the bf16 MFMA GEMM kernel for one tile shape (SmallDeepTile, see gemm_bf16_kernel.h).
+#include "gemm_bf16_kernel.h"
+
+namespace mtf {
+
+int launch_small_deep(const GemmDesc& d, const GemmArgs& a, int batch, hipStream_t s) {
+  return launch_cfg<SmallDeepTile>(d, a, batch, s);
+}
+
+}  // namespace mtf

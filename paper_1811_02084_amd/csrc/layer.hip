@@ -137,8 +137,6 @@ int ffn_bwd(const mtf_ffn_dims* d, const void* x, const void* a, const void* w_i
             const void* dy, void* dw_in, void* dw_out, const Partials& dx, void* dh, hipStream_t s,
             void* dbias = nullptr, void* red_ws = nullptr, size_t red_ws_bytes = 0) {
   const int64_t T = d->batch * d->length, D = d->d_model, F = d->d_ff;
-  // dw_out = einsum(a[b,l,F], dy[b,l,D] -> [F,D])
-  if (int rc = gemm_bf16_launch(gemm(a, false, dy, false, dw_out, false, F, D, T), s)) return rc;
   // dh = einsum(dy[b,l,D], w_out[F,D] -> [b,l,F]) * [a > 0]
   GemmDesc g = gemm(dy, true, w_out, true, dh, true, T, F, D);
   g.epi = MTF_EPI_MASK_GT0;
@@ -149,8 +147,12 @@ int ffn_bwd(const mtf_ffn_dims* d, const void* x, const void* a, const void* w_i
     if (int rc = reduce_cols_sum(static_cast<const bf16_t*>(dh), static_cast<float*>(dbias), T, F, red_ws,
                                  red_ws_bytes, s))
       return rc;
-  // dw_in = einsum(x[b,l,D], dh[b,l,F] -> [D,F])
-  if (int rc = gemm_bf16_launch(gemm(x, false, dh, false, dw_in, false, D, F, T), s)) return rc;
+  // dw_out = einsum(a[b,l,F], dy[b,l,D] -> [F,D]) and dw_in = einsum(x[b,l,D], dh[b,l,F] -> [D,F]):
+  // two outputs of D * F elements that each reduce out the token dims.  Alone, either has too few
+  // large tiles for the machine; as one grouped launch they fill it.
+  GemmDesc dw = gemm(a, false, dy, false, dw_out, false, F, D, T);
+  add_to_group(&dw, gemm(x, false, dh, false, dw_in, false, D, F, T));
+  if (int rc = gemm_bf16_launch(dw, s)) return rc;
   // dx_partial = einsum(dh[b,l,F], w_in[D,F] -> [b,l,D])
   return gemm_k_split(dh, true, w_in, true, dx, T, D, F, s);
 }
