@@ -5,7 +5,7 @@ One step = one pass of the whole hot path over one batch of synthetic input: for
 backward of a full Transformer-layer shard (attention + feed-forward sublayers with their
 residual adds), every contraction in the library's HIP kernels.  Prints ONE JSON line.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload layer|ffn|ffn_bias|mha|mesh|attention_lm|vocab|reshape]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload layer|ffn|ffn_bias|mha|mesh|mesh3d|attention_lm|vocab|reshape]
 
 `--workload copy` is not a benchmark of the path: it launches the library's plain copy kernel
 (fp32 -> fp32 cast) on a buffer of known size, which is what the HBM counters of a profiler run
@@ -41,7 +41,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="layer", choices=["layer", "ffn", "ffn_bias", "mha", "mesh", "attention_lm", "vocab", "reshape", "copy"])
+    ap.add_argument("--workload", default="layer", choices=["layer", "ffn", "ffn_bias", "mha", "mesh", "mesh3d", "attention_lm", "vocab", "reshape", "copy"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--graph", action="store_true",
                     help="time replays of one captured HIP graph of the step instead of eager launches")
@@ -129,6 +129,47 @@ def main():
         def step():
             parts = {c: mtf.ffn_fwd(xs[c], wi[c], wo[c])[1] for c in coords}
             return [mtf.reduce_partials([parts[(r, c)] for c in range(4)]) for r in range(4)]
+    elif args.workload == "mesh3d":
+        # config 7: the worked example's 3-D layout (batch -> rows, d_ff -> cols, d_model -> planes) on
+        # a VIRTUAL 2x2x2 mesh held on this one GPU, forward and backward: on every processor each of
+        # the six einsums leaves a partial sum (section "Data-Parallel, Model-Parallel Layouts",
+        # last layout), which the reduce kernel sums over the mesh dim the einsum's plan names; the
+        # ReLU and its mask are component-wise passes between them
+        cfg = mtf_inputs.config7()
+        mesh, layout = cfg["mesh"], cfg["layout"]
+        B, L, D = cfg["x"].shape
+        F = cfg["w_in"].shape[1]
+        fwd = flops_ffn(B * L, D, F)
+        name = (f"config 7: FFN fwd+bwd on a virtual 2x2x2 mesh (3-D layout), x[{B},{L},{D}] d_ff={F}: "
+                "8 processors x 6 einsums, every one a partial sum + grouped reduce")
+        g = {k: v.to(dev) for k, v in cfg.items() if torch.is_tensor(v)}
+        coords = [(r, c, p) for r in range(2) for c in range(2) for p in range(2)]
+        X, WI, WO, HID = ("batch", "length", "d_model"), ("d_model", "d_ff"), ("d_ff", "d_model"), ("batch", "length", "d_ff")
+        sl = lambda n, dims: {c: mtf.slice_copy(g[n], dims, mesh, layout, c) for c in coords}
+        xs, wi, wo, dys = sl("x", X), sl("w_in", WI), sl("w_out", WO), sl("dy", X)
+        sizes = dict(zip(X, (B, L, D)))
+        sizes["d_ff"] = F
+        shp = lambda dims: [(d, sizes[d]) for d in dims]
+        axes = lambda p, q, o: tuple(mtf.einsum_plan(shp(p), shp(q), shp(o), mesh, layout)["reduce_axes"])
+        plan = {k: axes(*v) for k, v in dict(h=(X, WI, HID), y=(HID, WO, X), dwo=(HID, X, WO), da=(X, WO, HID),
+                                             dwi=(X, HID, WI), dx=(HID, WI, X)).items()}
+        group = lambda c, ax: [c2 for c2 in coords if all(c2[i] == c[i] for i in range(3) if i not in ax)]
+        f32, bf16 = torch.float32, torch.bfloat16
+
+        def reduced(parts, ax, dt):
+            return {c: mtf.reduce_partials([parts[c2] for c2 in group(c, ax)], out_dtype=dt) for c in coords}
+
+        def step():
+            es = mtf.einsum_local
+            h = reduced({c: es(xs[c], X, wi[c], WI, HID, out_dtype=f32) for c in coords}, plan["h"], bf16)
+            a = {c: es(h[c], HID, None, None, HID, epi=mtf.EPI_RELU) for c in coords}
+            y = reduced({c: es(a[c], HID, wo[c], WO, X, out_dtype=f32) for c in coords}, plan["y"], f32)
+            dwo = reduced({c: es(a[c], HID, dys[c], X, WO, out_dtype=f32) for c in coords}, plan["dwo"], f32)
+            da = reduced({c: es(dys[c], X, wo[c], WO, HID, out_dtype=f32) for c in coords}, plan["da"], bf16)
+            dh = {c: es(da[c], HID, None, None, HID, epi=mtf.EPI_MASK_GT0, aux=a[c]) for c in coords}
+            dwi = reduced({c: es(xs[c], X, dh[c], HID, WI, out_dtype=f32) for c in coords}, plan["dwi"], f32)
+            dx = reduced({c: es(dh[c], HID, wi[c], WI, X, out_dtype=f32) for c in coords}, plan["dx"], f32)
+            return y, dwo, dwi, dx
     elif args.workload == "attention_lm":
         # the attention core at the head width of the paper's language models (d_k = d_v = 256):
         # 8 local heads of width 256 (the same 2048 columns as config 5), causal, 8 x 512 tokens
@@ -391,7 +432,7 @@ def cpu_baseline(workload, cfg):
     from oracle.layer import B, L, D, F, H, K, V
 
     f64 = lambda t: t.double().numpy()
-    nb = {"layer": 4, "mesh": 64}.get(workload, 2)   # batch elements in the sample (~5-10 s of host work)
+    nb = {"layer": 4, "mesh": 64, "mesh3d": 16}.get(workload, 2)   # batch elements in the sample (~5-10 s of host work)
     if workload == "vocab":
         return cpu_baseline_vocab(cfg, nb)
     if workload == "mesh":                           # the unsplit forward on the first batch elements
@@ -423,10 +464,10 @@ def cpu_baseline(workload, cfg):
                           f"(numpy; {dt:.1f} s)"}
     x = NT(f64(cfg["x"][:nb]), (B, L, D))
     t0 = time.perf_counter()
-    if workload in ("ffn", "ffn_bias"):
+    if workload in ("ffn", "ffn_bias", "mesh3d"):      # mesh3d: the unsplit layer the mesh computes
         w_in, w_out = NT(f64(cfg["w_in"]), (D, F)), NT(f64(cfg["w_out"]), (F, D))
         dy = NT(f64(cfg["dy"][:nb]), (B, L, D))
-        if workload == "ffn":
+        if workload != "ffn_bias":
             f = OL.ffn_fwd(x, w_in, w_out)
             OL.ffn_bwd(x, f["a"], w_in, w_out, dy)
         else:

@@ -151,8 +151,10 @@ int mtf_slice_copy(void* full, void* slice, const mtf_shape* t, const mtf_place*
  * Shapes are LOCAL (what mtf_einsum_plan returned); names decide everything (einsum paragraph
  * of "Operation Implementation").  in_dt is the dtype of a, b and aux; accumulation is fp32.
  * accumulate != 0 adds to the existing out (read in out_dt) before the epilogue.
- * bf16 operands whose dims fold to a (batched) matrix product run on MFMA; anything else runs
- * on a generic fp32 FMA kernel.  b may be NULL (one-operand einsum: reductions, transposes).
+ * bf16 operands whose dims fold to a (batched) matrix product run on MFMA; a one-operand einsum
+ * that keeps every dim in place (a component-wise operation: scale, ReLU, mask) runs as a
+ * vectorised pass; anything else runs on a generic fp32 FMA kernel.  b may be NULL (one-operand
+ * einsum: component-wise operations, reductions, transposes).
  * Errors: NULL, RANK, DUP_DIM, SIZE_MISMATCH, OUT_NOT_SUBSET, ALIGN, UNSUPPORTED, HIP. */
 int mtf_einsum_local(const void* a, const mtf_shape* a_local, const void* b,
                      const mtf_shape* b_local, void* out, const mtf_shape* out_local,
@@ -169,6 +171,7 @@ int mtf_einsum_local(const void* a, const mtf_shape* a_local, const void* b,
  * looks at shapes and addresses, launches nothing, needs no GPU. */
 #define MTF_PATH_GENERIC 0
 #define MTF_PATH_MFMA 1
+#define MTF_PATH_COMPONENTWISE 2 /* one operand, every dim kept in place: a vectorised HBM-bound pass */
 int mtf_einsum_local_path(const void* a, const mtf_shape* a_local, const void* b,
                           const mtf_shape* b_local, void* out, const mtf_shape* out_local,
                           mtf_dtype in_dt, mtf_dtype out_dt, mtf_epilogue epi, const void* aux,

@@ -135,3 +135,13 @@ def config6():
     d = vocab_inputs(6, 16, 256, 1024, 2048, 32768)
     d["vocab_offset"] = 2048
     return d
+
+
+def config7():
+    """The worked example's 3-D layout at shard size: batch -> rows, d_ff -> cols, d_model -> planes on
+    a 2 x 2 x 2 mesh; every processor holds x[16, 256, 512], W_in[512, 4096], W_out[4096, 512] (the
+    token and d_ff extents of config 2, d_model halved by the third mesh dim)."""
+    d = ffn_inputs(7, 32, 256, 1024, 8192, 8192)
+    d.update(mesh=[("rows", 2), ("cols", 2), ("planes", 2)],
+             layout=[("batch", "rows"), ("d_ff", "cols"), ("d_model", "planes")])
+    return d

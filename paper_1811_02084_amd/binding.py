@@ -274,7 +274,7 @@ def einsum_local(a, a_dims, b, b_dims, out_dims, out_dtype=None, epi=EPI_NONE, a
     return out
 
 
-PATH_GENERIC, PATH_MFMA = 0, 1
+PATH_GENERIC, PATH_MFMA, PATH_COMPONENTWISE = 0, 1, 2
 
 
 def einsum_local_path(a_dims, b_dims, out_dims, in_dtype=torch.bfloat16, out_dtype=torch.float32, epi=EPI_NONE,

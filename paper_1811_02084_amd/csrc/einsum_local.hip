@@ -75,6 +75,86 @@ __global__ void __launch_bounds__(256) einsum_generic_kernel(const InT* __restri
   }
 }
 
+// Component-wise operation on one tensor (section "Operation Implementation", component-wise
+// paragraph: same dims in and out, purely local): out = epilogue(alpha * a (+ out)).  8 elements
+// per thread, 16-byte accesses; HBM-bound.
+template <typename InT, typename OutT>
+__global__ void __launch_bounds__(256) componentwise_kernel(const InT* __restrict__ a, OutT* __restrict__ out,
+                                                           const InT* __restrict__ aux, int64_t count, float alpha,
+                                                           int accumulate, int epi) {
+  auto load8 = [](const void* p, int64_t i, bool bf16, float* v) {
+    if (bf16) {
+      const uint4 w = *reinterpret_cast<const uint4*>(static_cast<const bf16_t*>(p) + i);
+      const uint32_t u[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        v[2 * e] = __uint_as_float(u[e] << 16);
+        v[2 * e + 1] = __uint_as_float(u[e] & 0xffff0000u);
+      }
+    } else {
+      const float4 lo = *reinterpret_cast<const float4*>(static_cast<const float*>(p) + i);
+      const float4 hi = *reinterpret_cast<const float4*>(static_cast<const float*>(p) + i + 4);
+      v[0] = lo.x; v[1] = lo.y; v[2] = lo.z; v[3] = lo.w;
+      v[4] = hi.x; v[5] = hi.y; v[6] = hi.z; v[7] = hi.w;
+    }
+  };
+  for (int64_t i = (blockIdx.x * (int64_t)blockDim.x + threadIdx.x) * 8; i < count;
+       i += (int64_t)gridDim.x * blockDim.x * 8) {
+    float v[8], m[8], o[8];
+    load8(a, i, sizeof(InT) == 2, v);
+    if (epi == MTF_EPI_MASK_GT0) load8(aux, i, sizeof(InT) == 2, m);
+    if (accumulate) load8(out, i, sizeof(OutT) == 2, o);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      float r = alpha * v[e];
+      if (accumulate) r += o[e];
+      if (epi == MTF_EPI_RELU) r = fmaxf(r, 0.f);
+      if (epi == MTF_EPI_MASK_GT0) r = m[e] > 0.f ? r : 0.f;
+      v[e] = r;
+    }
+    if (sizeof(OutT) == 2) {
+      *reinterpret_cast<uint4*>(reinterpret_cast<bf16_t*>(out) + i) =
+          make_uint4(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]), pack_bf16x2(v[4], v[5]), pack_bf16x2(v[6], v[7]));
+    } else {
+      *reinterpret_cast<float4*>(reinterpret_cast<float*>(out) + i) = make_float4(v[0], v[1], v[2], v[3]);
+      *reinterpret_cast<float4*>(reinterpret_cast<float*>(out) + i + 4) = make_float4(v[4], v[5], v[6], v[7]);
+    }
+  }
+}
+
+// True when the one-operand einsum keeps every dim in place: a component-wise operation.
+bool is_componentwise(const Dims& da, const Dims& dout, int epi, int64_t* count) {
+  if (da.rank != dout.rank) return false;
+  int64_t n = 1;
+  for (int i = 0; i < da.rank; ++i) {
+    if (!same(da.name[i], dout.name[i])) return false;
+    n *= da.size[i];
+  }
+  *count = n;
+  return n % 8 == 0 && (epi == MTF_EPI_NONE || epi == MTF_EPI_RELU || epi == MTF_EPI_MASK_GT0);
+}
+
+int launch_componentwise(const void* a, void* out, int64_t count, mtf_dtype in_dt, mtf_dtype out_dt, int epi,
+                         const void* aux, float alpha, int accumulate, hipStream_t stream) {
+  const int blocks = (int)std::min<int64_t>(ceil_div(count / 8, 256), 256 * 16);
+  const double bytes = (double)count * ((in_dt == MTF_BF16 ? 2 : 4) * (epi == MTF_EPI_MASK_GT0 ? 2 : 1) +
+                                        (out_dt == MTF_BF16 ? 2 : 4) * (accumulate ? 2 : 1));
+  LaunchTimer timer("componentwise_kernel", 0, bytes, stream);
+  if (in_dt == MTF_F32 && out_dt == MTF_F32)
+    componentwise_kernel<float, float><<<blocks, 256, 0, stream>>>((const float*)a, (float*)out, (const float*)aux,
+                                                                 count, alpha, accumulate, epi);
+  else if (in_dt == MTF_F32)
+    componentwise_kernel<float, bf16_t><<<blocks, 256, 0, stream>>>((const float*)a, (bf16_t*)out, (const float*)aux,
+                                                                  count, alpha, accumulate, epi);
+  else if (out_dt == MTF_F32)
+    componentwise_kernel<bf16_t, float><<<blocks, 256, 0, stream>>>((const bf16_t*)a, (float*)out, (const bf16_t*)aux,
+                                                                  count, alpha, accumulate, epi);
+  else
+    componentwise_kernel<bf16_t, bf16_t><<<blocks, 256, 0, stream>>>((const bf16_t*)a, (bf16_t*)out,
+                                                                   (const bf16_t*)aux, count, alpha, accumulate, epi);
+  return launch_status("componentwise_kernel");
+}
+
 int launch_generic(const void* a, const Dims& da, const void* b, const Dims* db, void* out,
                    const Dims& dout, mtf_dtype in_dt, mtf_dtype out_dt, int epi, const void* aux,
                    float alpha, int accumulate, hipStream_t stream) {
@@ -272,6 +352,9 @@ extern "C" int mtf_einsum_local(const void* a, const mtf_shape* a_local, const v
     return rc;
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (r.use_gemm) return gemm_bf16_launch(r.gemm, s);
+  int64_t count = 0;
+  if (!r.has_b && is_componentwise(r.da, r.dout, epi, &count))
+    return launch_componentwise(a, out, count, in_dt, out_dt, epi, aux, alpha, accumulate, s);
   return launch_generic(a, r.da, r.has_b ? b : nullptr, r.has_b ? &r.db : nullptr, out, r.dout, in_dt, out_dt,
                         epi, aux, alpha, accumulate, s);
 }
@@ -283,5 +366,7 @@ extern "C" int mtf_einsum_local_path(const void* a, const mtf_shape* a_local, co
   EinsumRoute r;
   if (int rc = route_einsum(a, a_local, b, b_local, out, out_local, in_dt, out_dt, epi, aux, alpha, accumulate, &r))
     return rc;
-  return r.use_gemm ? MTF_PATH_MFMA : MTF_PATH_GENERIC;
+  int64_t count = 0;
+  if (r.use_gemm) return MTF_PATH_MFMA;
+  return !r.has_b && is_componentwise(r.da, r.dout, epi, &count) ? MTF_PATH_COMPONENTWISE : MTF_PATH_GENERIC;
 }

@@ -98,7 +98,10 @@ int gemm_bf16_launch(const GemmDesc& d, hipStream_t stream) {
   const double block_us = 7.8 * k_total / 1024.0;
   const int64_t large_tiles = count(256, 256), medium_tiles = count(256, 128), small_tiles = count(128, 128);
   const double cost_large = (double)ceil_div(large_tiles, 256) * (4.0 * block_us + 5.0);
-  const double cost_small = (double)ceil_div(small_tiles, 512) * (2.0 * block_us / 0.8 + 2.0);
+  // small tiles: two workgroups share a CU (a round of 512 takes two blocks' time at 0.8 of the
+  // rate); with at most one per CU a workgroup of 4 waves runs alone, at about 0.55
+  const double cost_small = small_tiles <= 256 ? block_us / 0.55 + 2.0
+                                               : (double)ceil_div(small_tiles, 512) * (2.0 * block_us / 0.8 + 2.0);
   // the narrow tile in two k-groups keeps its rate only when A is read along k
   const double cost_split = (double)ceil_div(medium_tiles, 256) * (2.0 * block_us / (d.a_kcontig ? 0.9 : 0.8) + 6.0);
   int tile = d.tile;

@@ -116,3 +116,98 @@ def test_config4_virtual_4x4_mesh_full_size():
         err = m2(got, ref)
         print(f"    column {col}: max rel err {err:.3e} over {n_tok} tokens", flush=True)
         assert err <= BF16_TOL, col
+
+
+def _mesh3d_tools(g, mesh, layout, coords):
+    """Helpers for running the feed-forward sublayer on the 3-D layout, processor by processor
+    through the library: slices of the inputs, the Allreduce mesh dims of an einsum from its
+    plan, and the grouped reduce of per-processor partial sums."""
+    sizes = dict(zip(X, g["x"].shape))
+    sizes[F] = g["w_in"].shape[1]
+    shp = lambda dims: [(d, sizes[d]) for d in dims]
+    axes = lambda p, q, out: mtf.einsum_plan(shp(p), shp(q), shp(out), mesh, layout)["reduce_axes"]
+    group = lambda c, ax: [c2 for c2 in coords if all(c2[i] == c[i] for i in range(len(mesh)) if i not in ax)]
+    sl = lambda name, dims: {c: mtf.slice_copy(g[name], dims, mesh, layout, c) for c in coords}
+    reduced = lambda parts, ax, dtype: {c: mtf.reduce_partials([parts[c2] for c2 in group(c, ax)], out_dtype=dtype)
+                                        for c in coords}
+    return axes, sl, reduced
+
+
+def _mesh3d_forward(g, mesh, layout, coords):
+    """Every einsum leaves partial sums (section "Data-Parallel, Model-Parallel Layouts", last
+    layout), each summed over the mesh dim its plan names; the ReLU is a component-wise operation
+    applied once the hidden layer's sum is complete.  Returns per-processor a and y."""
+    axes, sl, reduced = _mesh3d_tools(g, mesh, layout, coords)
+    xs, wi, wo = sl("x", X), sl("w_in", WI), sl("w_out", WO)
+    ax_h, ax_y = axes(X, WI, HID), axes(HID, WO, X)
+    assert ax_h == [2] and ax_y == [1]                          # over planes, then over cols
+    h = reduced({c: mtf.einsum_local(xs[c], X, wi[c], WI, HID, out_dtype=torch.float32) for c in coords}, ax_h,
+                torch.bfloat16)
+    a = {c: mtf.einsum_local(h[c], HID, None, None, HID, epi=mtf.EPI_RELU) for c in coords}
+    y = reduced({c: mtf.einsum_local(a[c], HID, wo[c], WO, X, out_dtype=torch.float32) for c in coords}, ax_y,
+                torch.float32)
+    return dict(a=a, y=y)
+
+
+def _mesh3d_backward(g, mesh, layout, coords, a):
+    """Backward from given per-processor activations `a`: four more einsums, each a partial sum."""
+    axes, sl, reduced = _mesh3d_tools(g, mesh, layout, coords)
+    xs, wi, wo, dys = sl("x", X), sl("w_in", WI), sl("w_out", WO), sl("dy", X)
+    ax_dwo, ax_da, ax_dwi, ax_dx = axes(HID, X, WO), axes(X, WO, HID), axes(X, HID, WI), axes(HID, WI, X)
+    assert ax_dwo == [0] and ax_da == [2] and ax_dwi == [0] and ax_dx == [1]   # rows, planes, rows, cols
+    out = {}
+    out["dw_out"] = reduced({c: mtf.einsum_local(a[c], HID, dys[c], X, WO, out_dtype=torch.float32) for c in coords},
+                            ax_dwo, torch.float32)
+    da = reduced({c: mtf.einsum_local(dys[c], X, wo[c], WO, HID, out_dtype=torch.float32) for c in coords}, ax_da,
+                 torch.bfloat16)
+    dh = {c: mtf.einsum_local(da[c], HID, None, None, HID, epi=mtf.EPI_MASK_GT0, aux=a[c]) for c in coords}
+    out["dw_in"] = reduced({c: mtf.einsum_local(xs[c], X, dh[c], HID, WI, out_dtype=torch.float32) for c in coords},
+                           ax_dwi, torch.float32)
+    out["dx"] = reduced({c: mtf.einsum_local(dh[c], HID, wi[c], WI, X, out_dtype=torch.float32) for c in coords},
+                        ax_dx, torch.float32)
+    return out
+
+
+def test_three_dimensional_layout_at_shard_size_bf16():
+    """The last layout of the worked example (batch -> rows, hidden -> cols, io -> planes) at shard
+    size in bf16: every processor's einsums run on the matrix-core kernel on its slices
+    (x[16,256,512], w[512,4096], v[4096,512]), every einsum's partial sums are reduced over the
+    mesh dim its plan names, and the assembled result is compared with the oracle's unsplit layer."""
+    cfg = mtf_inputs.config7()
+    g = on_device(cfg)
+    mesh, layout = cfg["mesh"], cfg["layout"]
+    coords = OLY.all_coords(mesh)
+    # each local einsum of this layout takes the matrix-core path
+    for a_d, b_d, o_d, a_s, b_s, o_s in (
+            (X, WI, HID, (16, 256, 512), (512, 4096), (16, 256, 4096)),
+            (HID, WO, X, (16, 256, 4096), (4096, 512), (16, 256, 512)),
+            (HID, X, WO, (16, 256, 4096), (16, 256, 512), (4096, 512)),
+            (X, HID, WI, (16, 256, 512), (16, 256, 4096), (512, 4096))):
+        assert mtf.einsum_local_path(list(zip(a_d, a_s)), list(zip(b_d, b_s)), list(zip(o_d, o_s))) == mtf.PATH_MFMA
+    print("3-D layout: 8 processors, forward", flush=True)
+    fwd = _mesh3d_forward(g, mesh, layout, coords)
+    x, w_in, w_out, dy = (named(cfg["x"], X), named(cfg["w_in"], WI), named(cfg["w_out"], WO), named(cfg["dy"], X))
+    print("3-D layout: oracle, unsplit", flush=True)
+    ref = OL.ffn_fwd(x, w_in, w_out)
+    for c in coords:
+        for k, dims in (("a", HID), ("y", X)):
+            want = OLY.slice_tensor(ref[k], mesh, layout, c)
+            err = m2(f64(fwd[k][c]), want.data)
+            assert err <= BF16_TOL, (k, c, err)
+    # processors that differ only along the reduced mesh dim end with identical sums
+    assert torch.equal(fwd["y"][(0, 0, 0)], fwd["y"][(0, 1, 0)])
+    # backward from the oracle's activation (the ReLU mask is then the same bits on both sides)
+    print("3-D layout: backward", flush=True)
+    a_ref = {c: to_dev_bf16(OLY.slice_tensor(ref["a"], mesh, layout, c).data) for c in coords}
+    refb = OL.ffn_bwd(x, ref["a"], w_in, w_out, dy)
+    got = _mesh3d_backward(g, mesh, layout, coords, a_ref)
+    for c in coords:
+        for k, dims in (("dw_in", WI), ("dw_out", WO), ("dx", X)):
+            want = OLY.slice_tensor(refb[k], mesh, layout, c)
+            err = m2(f64(got[k][c]), want.data)
+            assert err <= BF16_TOL, (k, c, err)
+    print("3-D layout: all slices within tolerance", flush=True)
+
+
+def to_dev_bf16(arr):
+    return torch.from_numpy(np.ascontiguousarray(arr)).to(torch.bfloat16).cuda()

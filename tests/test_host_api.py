@@ -216,6 +216,10 @@ def test_einsum_local_path_reports_the_kernel_that_would_run():
     assert P(shp(X, (2, 8, 16)), shp(W, (16, 64)), shp(Hd, (2, 8, 64)), in_dtype=torch.float32) == mtf.PATH_GENERIC
     assert P(shp(X, (2, 8, 20)), shp(W, (20, 64)), shp(Hd, (2, 8, 64))) == mtf.PATH_GENERIC
     assert P(shp(X, (2, 8, 16)), None, [("d_model", 16)]) == mtf.PATH_GENERIC
+    # one operand, dims kept in place: the component-wise pass (whole 16-byte vectors only)
+    assert P(shp(X, (2, 8, 16)), None, shp(X, (2, 8, 16)), epi=mtf.EPI_RELU) == mtf.PATH_COMPONENTWISE
+    assert P(shp(X, (2, 8, 16)), None, shp(("length", "batch", "d_model"), (8, 2, 16))) == mtf.PATH_GENERIC
+    assert P(shp(X, (3, 1, 5)), None, shp(X, (3, 1, 5))) == mtf.PATH_GENERIC
     # misaligned operand address: reported as the error the einsum itself would give
     with pytest.raises(mtf.MtfError) as e:
         P(shp(X, (2, 8, 16)), shp(W, (16, 64)), shp(Hd, (2, 8, 64)), a_ptr=0x1004)
