@@ -1,4 +1,4 @@
-// Launcher interface of the fused softmax-attention kernels (gfx950, head width 128).
+// Launcher interface of the fused softmax-attention kernels (gfx950, head width 128 or 256).
 #pragma once
 #include <hip/hip_runtime.h>
 
@@ -6,12 +6,14 @@
 
 namespace mtf {
 
-constexpr int kHeadDim = 128;  // d_k = d_v supported by the fused kernels
+// d_k = d_v the fused kernels support: 128 (the translation models of the paper's experiments)
+// and 256 (its language models).
+bool attn_fused_width(int64_t head_dim);
 
 // All tensors use the einsum layouts of the layer: q, k, v, ctx, dctx, dq, dk, dv are
-// [batch, length, heads, 128] bf16; lse and delta are [batch, heads, length] fp32.
+// [batch, length, heads, head_dim] bf16; lse and delta are [batch, heads, length] fp32.
 struct AttnShape {
-  int batch, length, heads;
+  int batch, length, heads, head_dim;
   float scale;
   int causal;
 };

@@ -149,8 +149,8 @@ int check_dims(const mtf_mha_dims* d) {
   if (d->batch <= 0 || d->length <= 0 || d->heads <= 0 || d->d_k <= 0)
     return fail(MTF_ERR_SIZE_MISMATCH, "non-positive attention dim");
   if (d->d_k % 8) return fail(MTF_ERR_UNSUPPORTED, "attention needs d_k divisible by 8");
-  if (d->d_k != kHeadDim && d->length % 8)
-    return fail(MTF_ERR_UNSUPPORTED, "attention with d_k != %d needs length divisible by 8", kHeadDim);
+  if (!attn_fused_width(d->d_k) && d->length % 8)
+    return fail(MTF_ERR_UNSUPPORTED, "attention at head widths other than 128 and 256 needs length divisible by 8");
   if (d->batch > INT32_MAX || d->length > INT32_MAX || d->heads > INT32_MAX)
     return fail(MTF_ERR_UNSUPPORTED, "attention dim too large");
   return MTF_OK;
@@ -164,7 +164,7 @@ using namespace mtf;
 extern "C" {
 
 size_t mtf_attention_fwd_workspace_bytes(const mtf_mha_dims* d) {
-  if (check_dims(d) || d->d_k == kHeadDim) return 0;
+  if (check_dims(d) || attn_fused_width(d->d_k)) return 0;
   const Geometry g = geometry(d);
   // logits fp32, exponentials bf16, 1 / row sums fp32
   return round256((size_t)g.sq * 4) + round256((size_t)g.sq * 2) + round256((size_t)g.B * g.H * g.L * 4);
@@ -177,8 +177,8 @@ int mtf_attention_fwd(const mtf_mha_dims* d, const void* q, const void* k, const
   if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(ctx) || !aligned16(lse) || !aligned16(workspace))
     return fail(MTF_ERR_ALIGN, "mtf_attention_fwd buffer");
   hipStream_t s = static_cast<hipStream_t>(stream);
-  if (d->d_k == kHeadDim) {
-    AttnShape as{(int)d->batch, (int)d->length, (int)d->heads, scale, causal};
+  if (attn_fused_width(d->d_k)) {
+    AttnShape as{(int)d->batch, (int)d->length, (int)d->heads, (int)d->d_k, scale, causal};
     return attn_fwd_launch(as, (const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (bf16_t*)ctx, (float*)lse, s);
   }
   const size_t need = mtf_attention_fwd_workspace_bytes(d);
@@ -206,7 +206,7 @@ int mtf_attention_fwd(const mtf_mha_dims* d, const void* q, const void* k, const
 size_t mtf_attention_bwd_workspace_bytes(const mtf_mha_dims* d) {
   if (check_dims(d)) return 0;
   const Geometry g = geometry(d);
-  if (d->d_k == kHeadDim) return round256((size_t)g.B * g.H * g.L * 4);  // delta
+  if (attn_fused_width(d->d_k)) return round256((size_t)g.B * g.H * g.L * 4);  // delta
   // logits, dp fp32; p, ds bf16; delta fp32
   return 2 * round256((size_t)g.sq * 4) + 2 * round256((size_t)g.sq * 2) + round256((size_t)g.B * g.H * g.L * 4);
 }
@@ -222,8 +222,8 @@ int mtf_attention_bwd(const mtf_mha_dims* d, const void* q, const void* k, const
   const size_t need = mtf_attention_bwd_workspace_bytes(d);
   if (!workspace || workspace_bytes < need) return fail(MTF_ERR_WORKSPACE, "mtf_attention_bwd needs %zu bytes", need);
   hipStream_t s = static_cast<hipStream_t>(stream);
-  if (d->d_k == kHeadDim) {
-    AttnShape as{(int)d->batch, (int)d->length, (int)d->heads, scale, causal};
+  if (attn_fused_width(d->d_k)) {
+    AttnShape as{(int)d->batch, (int)d->length, (int)d->heads, (int)d->d_k, scale, causal};
     return attn_bwd_launch(as, (const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (const bf16_t*)ctx,
                            (const float*)lse, (const bf16_t*)dctx, (bf16_t*)dq, (bf16_t*)dk, (bf16_t*)dv,
                            (float*)workspace, s);

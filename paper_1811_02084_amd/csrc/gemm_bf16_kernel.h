@@ -403,6 +403,26 @@ __global__ void __launch_bounds__(Cfg::kThreads, Cfg::kWavesPerSimd) gemm_bf16_k
     compute(std::false_type{}, total_tiles - 1, ring + stage * Cfg::kStage, nullptr, nullptr);
   }
 
+  // The epilogue stores the wave tile as 32-row slabs; with k-groups a wave stores its group's
+  // half of them.  The mask operand of a slab (the only global read on the epilogue's critical
+  // path) is requested one slab ahead, the first slab's before the barrier below - from clamped,
+  // always valid addresses, so that the loads need no branch around them.
+  auto my_slab = [&](int i) { return WK == 1 || (i / (TM / 2)) == kg; };
+  uint2 aux_v[2][8];
+  auto request_mask = [&](int i) {
+    const int out_row_ = lane >> 4, out_col_ = (lane & 15) * 4;
+#pragma unroll
+    for (int it = 0; it < 8; ++it) {
+      const int mc = min(m0 + wave_m + i * 32 + it * 4 + out_row_, M - 1);
+      const int nc = min(n0 + wave_n + out_col_, N - 4);  // N % 8 == 0
+      aux_v[i & 1][it] = *reinterpret_cast<const uint2*>(g.aux + offC + (int64_t)mc * ldc + nc);
+    }
+  };
+  if (EPI == MTF_EPI_MASK_GT0) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+      if (my_slab(i) && (i == 0 || !my_slab(i - 1))) request_mask(i);
+  }
   __syncthreads();  // everyone is done reading the last k-tile: the ring is free
   // ---- k-groups: the two waves at one tile position hold partial sums over disjoint k.  They
   // exchange halves through LDS (one 32-row slab per wave and round, lane-major so that every
@@ -468,21 +488,20 @@ __global__ void __launch_bounds__(Cfg::kThreads, Cfg::kWavesPerSimd) gemm_bf16_k
   }
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
-    if (WK == 2 && (i / (TM / 2)) != kg) continue;  // the other k-group stores this slab
-    // What the fused epilogues read from global memory (the mask operand, the old C) is requested
-    // for the whole slab before anything waits on it - from clamped, always valid addresses, so
-    // that the loads need no branch around them: one memory round trip per slab, hidden behind
-    // the slab's pass through LDS, instead of one per row group.
-    uint2 aux_v[8], old_bf[8];
+    if (!my_slab(i)) continue;  // the other k-group stores this slab
+    if (EPI == MTF_EPI_MASK_GT0 && i + 1 < TM && my_slab(i + 1)) request_mask(i + 1);
+    // The old C of an accumulating store is requested for the whole slab before anything waits on
+    // it (clamped addresses again): one memory round trip per slab, hidden behind the slab's pass
+    // through LDS, instead of one per row group.
+    uint2 old_bf[8];
     float4 old_f[8];
-    if (EPI == MTF_EPI_MASK_GT0 || g.accumulate) {
+    if (g.accumulate) {
 #pragma unroll
       for (int it = 0; it < 8; ++it) {
         const int mc = min(m0 + wave_m + i * 32 + it * 4 + out_row, M - 1);
         const int nc = min(n0 + wave_n + out_col, N - 4);  // N % 8 == 0
         const int64_t idc = offC + (int64_t)mc * ldc + nc;
-        if (EPI == MTF_EPI_MASK_GT0) aux_v[it] = *reinterpret_cast<const uint2*>(g.aux + idc);
-        if (g.accumulate) {
+        {
           if (OUT_BF16)
             old_bf[it] = *reinterpret_cast<const uint2*>(static_cast<const bf16_t*>(Cg) + idc);
           else
@@ -534,7 +553,8 @@ __global__ void __launch_bounds__(Cfg::kThreads, Cfg::kWavesPerSimd) gemm_bf16_k
         for (int e = 0; e < 4; ++e) v[e] = fmaxf(v[e], 0.f);
       } else if (EPI == MTF_EPI_MASK_GT0) {
         // bf16 > 0  <=>  sign bit clear and magnitude non-zero
-        const uint32_t w[4] = {aux_v[it].x & 0xffffu, aux_v[it].x >> 16, aux_v[it].y & 0xffffu, aux_v[it].y >> 16};
+        const uint2 mk = aux_v[i & 1][it];
+        const uint32_t w[4] = {mk.x & 0xffffu, mk.x >> 16, mk.y & 0xffffu, mk.y >> 16};
 #pragma unroll
         for (int e = 0; e < 4; ++e) v[e] = (w[e] != 0u && w[e] < 0x8000u) ? v[e] : 0.f;
       }

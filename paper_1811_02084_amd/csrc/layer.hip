@@ -93,7 +93,8 @@ int check_mha(const mtf_mha_dims* d) {
   if (!d) return fail(MTF_ERR_NULL, "dims");
   if (d->batch <= 0 || d->length <= 0 || d->d_model <= 0 || d->heads <= 0 || d->d_k <= 0)
     return fail(MTF_ERR_SIZE_MISMATCH, "non-positive attention dim");
-  if (d->d_k != kHeadDim) return fail(MTF_ERR_UNSUPPORTED, "fused attention needs d_k = d_v = %d", kHeadDim);
+  if (!attn_fused_width(d->d_k))
+    return fail(MTF_ERR_UNSUPPORTED, "the attention step needs d_k = d_v = 128 or 256, not %lld", (long long)d->d_k);
   if (d->d_model % 8) return fail(MTF_ERR_UNSUPPORTED, "attention step needs d_model divisible by 8");
   return MTF_OK;
 }
@@ -167,7 +168,7 @@ int mha_fwd(const mtf_mha_dims* d, const void* x, const void* w_q, const void* w
   add_to_group(&qkv, gemm(x, true, w_k, false, k, true, T, HK, D));
   add_to_group(&qkv, gemm(x, true, w_v, false, v, true, T, HK, D));
   if (int rc = gemm_bf16_launch(qkv, s)) return rc;
-  AttnShape as{(int)d->batch, (int)d->length, (int)d->heads, scale, causal};
+  AttnShape as{(int)d->batch, (int)d->length, (int)d->heads, (int)d->d_k, scale, causal};
   if (int rc = attn_fwd_launch(as, (const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (bf16_t*)ctx,
                                (float*)lse, s))
     return rc;
@@ -182,7 +183,7 @@ int mha_bwd(const mtf_mha_dims* d, const void* x, const void* w_q, const void* w
   const int64_t T = d->batch * d->length, D = d->d_model, HK = d->heads * d->d_k;
   // dctx = einsum(dy[b,l,D], w_o[h,v,D] -> [b,l,h,v])
   if (int rc = gemm_bf16_launch(gemm(dy, true, w_o, true, w.dctx, true, T, HK, D), s)) return rc;
-  AttnShape as{(int)d->batch, (int)d->length, (int)d->heads, scale, causal};
+  AttnShape as{(int)d->batch, (int)d->length, (int)d->heads, (int)d->d_k, scale, causal};
   if (int rc = attn_bwd_launch(as, (const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v,
                                (const bf16_t*)ctx, (const float*)lse, w.dctx, w.dq, w.dk, w.dv, w.delta, s))
     return rc;
