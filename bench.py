@@ -177,7 +177,7 @@ def main():
         causal, scale = True, 1.0 / math.sqrt(K)
         pairs = L * (L + 1) / 2
         fwd = 2 * 2.0 * B * H * pairs * K
-        name = f"attention core fwd+bwd, q/k/v[{B},{L},{H},{K}] causal (unfused: einsums + row softmax)"
+        name = f"attention core fwd+bwd, q/k/v[{B},{L},{H},{K}] causal (fused kernels at head width 256)"
         cfg = {n: mtf_inputs.normal(8, i, (B, L, H, K)) for i, n in enumerate(("q", "k", "v", "dctx"))}
         cfg.update(scale=scale, causal=causal)
         g = {n: (t.to(dev) if torch.is_tensor(t) else t) for n, t in cfg.items()}

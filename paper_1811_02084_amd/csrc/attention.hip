@@ -266,10 +266,10 @@ __device__ __forceinline__ QueryRows query_rows(int length, bool causal, int wav
 // wavefronts share a SIMD.  At 256 those fragments alone would fill the vector registers a wave
 // can address, so one of them stays in the wave's LDS slab and is fetched like the tile operands,
 // the K/V tiles shrink to 32 rows (the slabs need the LDS), and one wavefront has the SIMD.
-template <int HD, int NWAVES>
+template <int HD, int NWAVES, bool ROWS_IN_LDS>
 struct RowKernelShape {
-  static constexpr bool kRowsInLds = HD == 256;
-  static constexpr int kTR = kRowsInLds ? 32 : kTileRows;  // rows of a K/V tile
+  static constexpr bool kRowsInLds = ROWS_IN_LDS;
+  static constexpr int kTR = HD == 256 ? 32 : kTileRows;  // rows of a K/V tile
   static constexpr int kWavesPerSimd = (HD == 128 && NWAVES >= 4) ? 2 : 1;
   // Slabs get LDS of their own when they stay in use (rows in LDS) or when, with 8 waves, they
   // need as much as both stages; otherwise they borrow stage 1, which the pipeline first writes at
@@ -297,10 +297,10 @@ __device__ __forceinline__ void negate_slab(char* slab, int lane) {
 
 // One workgroup: NWAVES*32 query rows of one (batch, head); each wave owns 32 of them.
 template <int HD, int NWAVES>
-__global__ void __launch_bounds__(NWAVES * 64, (RowKernelShape<HD, NWAVES>::kWavesPerSimd)) attn_fwd_kernel(AttnArgs a) {
-  __shared__ __attribute__((aligned(1024))) char lds[RowKernelShape<HD, NWAVES>::kLdsBytes];
+__global__ void __launch_bounds__(NWAVES * 64, (RowKernelShape<HD, NWAVES, false>::kWavesPerSimd)) attn_fwd_kernel(AttnArgs a) {
   using G = Geo<HD>;
-  using S = RowKernelShape<HD, NWAVES>;
+  using S = RowKernelShape<HD, NWAVES, false>;
+  __shared__ __attribute__((aligned(1024))) char lds[S::kLdsBytes];
   constexpr int kTR = S::kTR, kTileBytes = S::kTileBytes, kSlabBytes = G::kSlabBytes, kKS = G::kKS, kBlk = G::kBlk;
   constexpr bool kQInLds = S::kRowsInLds;
   char* const stage0 = lds;                     // K tile, V tile
@@ -320,6 +320,11 @@ __global__ void __launch_bounds__(NWAVES * 64, (RowKernelShape<HD, NWAVES>::kWav
   const int q_lane = q0w + (lane & 31);  // this lane's query row
   const int kv_end = a.causal ? min(L, qr.last_row + 1) : L;
   const int n_tiles = (kv_end + kTR - 1) / kTR;
+  // Tiles this wave takes part in: under the causal mask its rows see nothing past their own
+  // position.  The rest of the workgroup's tiles it only helps to load, in a loop of their own: a
+  // bypass inside the processing loop would make the compiler carry the accumulators through
+  // copies around every tile.
+  const int my_tiles = !qr.active ? 0 : a.causal ? min(n_tiles, (q0w + 31) / kTR + 1) : n_tiles;
   auto issue = [&](int t, char* st) {
     load_tile<HD, NWAVES, kTR>(kb, (uint32_t)(rs * 2), t * kTR, L, st, wave, lane);
     load_tile<HD, NWAVES, kTR>(vb, (uint32_t)(rs * 2), t * kTR, L, st + kTileBytes, wave, lane);
@@ -361,10 +366,6 @@ __global__ void __launch_bounds__(NWAVES * 64, (RowKernelShape<HD, NWAVES>::kWav
   auto process = [&](int t, const char* st) {
     const int kv0 = t * kTR;
     const char *kt_ = st, *vt_ = st + kTileBytes;
-    // A wave with nothing visible in this tile skips it.  Not at width 256: the workgroup waits for
-    // its last wave either way, a hidden tile adds exact zeros, and the bypass would make the
-    // compiler carry the accumulators through ordinary registers around every tile.
-    if (!kQInLds && (!qr.active || (a.causal && kv0 > q0w + 31))) return;
     // Operand fragments are fetched from LDS kDepth MFMAs ahead of their use, through rings of
     // kDepth + 1 register buffers, and a scheduling barrier after each MFMA keeps that order: left
     // alone, the scheduler either sinks each read to just before its MFMA (which then waits out a
@@ -427,7 +428,7 @@ __global__ void __launch_bounds__(NWAVES * 64, (RowKernelShape<HD, NWAVES>::kWav
       const float alpha = __builtin_amdgcn_exp2f(m2 - m_new);
       lsum *= alpha;
       m2 = m_new;
-      if (kQInLds) {
+      if (HD == 256) {
         // One wavefront per SIMD: the accumulators live in the accumulation registers, which the
         // vector ALU cannot multiply in place.  Written as plain C++ the compiler carries them
         // through ordinary registers around every tile's matrix instructions for the sake of this
@@ -478,12 +479,16 @@ __global__ void __launch_bounds__(NWAVES * 64, (RowKernelShape<HD, NWAVES>::kWav
   };
   // Two stages: the tile after the one being processed is in flight.  Passing the barrier means
   // everyone has the current tile and is done with the stage the next issue() overwrites.
-  for (int t = 0; t < n_tiles; ++t) {
+  for (int t = 0; t < my_tiles; ++t) {
     char* cur = (t & 1) ? stage1 : stage0;
     char* nxt = (t & 1) ? stage0 : stage1;
     wait_loads_then_barrier();
     if (t + 1 < n_tiles) issue(t + 1, nxt);
     process(t, cur);
+  }
+  for (int t = my_tiles; t < n_tiles; ++t) {  // tiles only later waves of the workgroup can see
+    wait_loads_then_barrier();
+    if (t + 1 < n_tiles) issue(t + 1, (t & 1) ? stage0 : stage1);
   }
   if (!S::kOwnSlabs) __syncthreads();  // stage 1 may still be read by a slower wave
   if (!qr.active) return;
@@ -497,9 +502,9 @@ __global__ void __launch_bounds__(NWAVES * 64, (RowKernelShape<HD, NWAVES>::kWav
 // delta[b,h,l] = sum_d dctx[b,l,h,d] * ctx[b,l,h,d] (= sum_m p * dp of the softmax Jacobian) for
 // its rows, which the dk/dv kernel launched after it reads.
 template <int HD, int NWAVES>
-__global__ void __launch_bounds__(NWAVES * 64, (RowKernelShape<HD, NWAVES>::kWavesPerSimd)) attn_dq_kernel(AttnArgs a) {
+__global__ void __launch_bounds__(NWAVES * 64, (RowKernelShape<HD, NWAVES, HD == 256>::kWavesPerSimd)) attn_dq_kernel(AttnArgs a) {
   using G = Geo<HD>;
-  using S = RowKernelShape<HD, NWAVES>;
+  using S = RowKernelShape<HD, NWAVES, HD == 256>;
   constexpr int kTR = S::kTR, kTileBytes = S::kTileBytes, kSlabBytes = G::kSlabBytes, kKS = G::kKS, kBlk = G::kBlk;
   constexpr bool kDoInLds = S::kRowsInLds;  // the dctx rows stay in the slab (q is kept in registers)
   __shared__ __attribute__((aligned(1024))) char stage0[2 * kTileBytes];  // K tile, V tile
@@ -520,6 +525,11 @@ __global__ void __launch_bounds__(NWAVES * 64, (RowKernelShape<HD, NWAVES>::kWav
   const int q_load = min(q_lane, L - 1);
   const int kv_end = a.causal ? min(L, qr.last_row + 1) : L;
   const int n_tiles = (kv_end + kTR - 1) / kTR;
+  // Tiles this wave takes part in: under the causal mask its rows see nothing past their own
+  // position.  The rest of the workgroup's tiles it only helps to load, in a loop of their own: a
+  // bypass inside the processing loop would make the compiler carry the accumulators through
+  // copies around every tile.
+  const int my_tiles = !qr.active ? 0 : a.causal ? min(n_tiles, (q0w + 31) / kTR + 1) : n_tiles;
   auto issue = [&](int t, char* st) {
     load_tile<HD, NWAVES, kTR>(kb, (uint32_t)(rs * 2), t * kTR, L, st, wave, lane);
     load_tile<HD, NWAVES, kTR>(vb, (uint32_t)(rs * 2), t * kTR, L, st + kTileBytes, wave, lane);
@@ -581,7 +591,6 @@ __global__ void __launch_bounds__(NWAVES * 64, (RowKernelShape<HD, NWAVES>::kWav
   auto process = [&](int t, const char* st) {
     const int kv0 = t * kTR;
     const char *kt_ = st, *vt_ = st + kTileBytes;
-    if (!S::kRowsInLds && (!qr.active || (a.causal && kv0 > q0w + 31))) return;  // as in the forward kernel
     constexpr int kKvb = kTR / 32, kT = kTR / 16;
     bf16x8 dsf[kT];
     // Pinning the fragment reads ahead of their MFMAs, as the forward kernel does, costs this
@@ -658,12 +667,16 @@ __global__ void __launch_bounds__(NWAVES * 64, (RowKernelShape<HD, NWAVES>::kWav
                                                             dq[blk], 0, 0, 0);
     }
   };
-  for (int t = 0; t < n_tiles; ++t) {
+  for (int t = 0; t < my_tiles; ++t) {
     char* cur = (t & 1) ? stage1 : stage0;
     char* nxt = (t & 1) ? stage0 : stage1;
     wait_loads_then_barrier();
     if (t + 1 < n_tiles) issue(t + 1, nxt);
     process(t, cur);
+  }
+  for (int t = my_tiles; t < n_tiles; ++t) {  // tiles only later waves of the workgroup can see
+    wait_loads_then_barrier();
+    if (t + 1 < n_tiles) issue(t + 1, (t & 1) ? stage0 : stage1);
   }
   if (!S::kOwnSlabs) __syncthreads();  // stage 1 may still be read by a slower wave
   if (!qr.active) return;
@@ -912,9 +925,9 @@ int attn_fwd_launch(const AttnShape& s, const bf16_t* q, const bf16_t* k, const 
   const double pairs = s.causal ? 0.5 * s.length * (s.length + 1.0) : (double)s.length * s.length;
   const double flops = 2.0 * 2.0 * s.batch * s.heads * pairs * s.head_dim;
   const double bytes = 4.0 * s.batch * s.length * s.heads * s.head_dim * 2;
-  if (s.head_dim == 256) {  // one wave per SIMD at this width: workgroups of 4 waves
-    LaunchTimer timer("attn_fwd_kernel<256, 4>", flops, bytes, stream);
-    attn_fwd_kernel<256, 4><<<row_block_grid(s, 4), 256, 0, stream>>>(a);
+  if (s.head_dim == 256) {  // one wave per SIMD at this width: two workgroups of 2 waves share a CU
+    LaunchTimer timer("attn_fwd_kernel<256, 2>", flops, bytes, stream);
+    attn_fwd_kernel<256, 2><<<row_block_grid(s, 2), 128, 0, stream>>>(a);
     return launch_status("attn_fwd_kernel");
   }
   const int nw = waves_per_group(s, 8);

@@ -50,7 +50,6 @@ struct GemmDesc {
   };
   int nextra = 0;
   Extra extra[kMaxGroup - 1];
-  int tile = 0;  // 0 = choose by output size, 1 = 128x128 tiles, 2 = 256x256 tiles, 3 = 128x128 with 4 stages
 };
 
 // True when the MFMA kernel can run this problem (alignment, divisibility of the leading dims by

@@ -5,7 +5,6 @@
 // computation time goes).
 #include "gemm_bf16_kernel.h"
 
-#include <cstdlib>
 
 namespace mtf {
 
@@ -104,20 +103,9 @@ int gemm_bf16_launch(const GemmDesc& d, hipStream_t stream) {
                                                : (double)ceil_div(small_tiles, 512) * (2.0 * block_us / 0.8 + 2.0);
   // the narrow tile in two k-groups keeps its rate only when A is read along k
   const double cost_split = (double)ceil_div(medium_tiles, 256) * (2.0 * block_us / (d.a_kcontig ? 0.9 : 0.8) + 6.0);
-  int tile = d.tile;
-  if (const char* force = std::getenv("MTF_TILE")) tile = std::atoi(force);  // TUNING ONLY (to be removed)
-  if (tile == 0) {
-    double best = cost_large;
-    tile = 2;
-    if (cost_split < best) best = cost_split, tile = 4;
-    if (cost_small < best) best = cost_small, tile = small_tiles <= 256 ? 3 : 1;
-  }
-  switch (tile) {
-    case 2: return launch_large(d, a, batch, stream);
-    case 3: return launch_small_deep(d, a, batch, stream);
-    case 4: return launch_split(d, a, batch, stream);
-    default: return launch_small(d, a, batch, stream);
-  }
+  if (cost_large <= cost_split && cost_large <= cost_small) return launch_large(d, a, batch, stream);
+  if (cost_split <= cost_small) return launch_split(d, a, batch, stream);
+  return small_tiles <= 256 ? launch_small_deep(d, a, batch, stream) : launch_small(d, a, batch, stream);
 }
 
 }  // namespace mtf

@@ -1,6 +1,6 @@
-"""The attention core at head widths other than 128 (the language models of the paper use
-d_k = d_v = 256): two einsums on the GEMM kernel with a row softmax between them, against the
-oracle; and the same entry points at width 128, where they run the fused kernels."""
+"""The attention core behind mtf_attention_fwd / mtf_attention_bwd against the oracle: the fused
+kernels at head widths 128 and 256 (the paper's translation and language models), and at any other
+width two einsums on the GEMM kernel with a row softmax between them."""
 import math
 
 import numpy as np
@@ -31,6 +31,9 @@ CASES = [  # batch, length, heads, d_k, causal
     (3, 200, 2, 32, False),
     (2, 72, 2, 128, True),       # the fused kernels behind the same entry points
     (4, 256, 8, 256, True),      # a shard of the LM variant: 8 heads of width 256
+    (2, 520, 4, 256, True),      # width 256 past one pass of row blocks, ragged tail of 8 rows
+    (1, 1, 1, 256, True),        # a single position
+    (1, 33, 2, 256, False),      # one row into the second 32-row tile
     (4, 200, 32, 128, True),     # fused kernels with 4 waves per workgroup (128 (batch, head) pairs), ragged
     (4, 256, 32, 128, False),
     (4, 384, 32, 128, True),     # 8-wave workgroups with an odd number of 128-row blocks (middle block unpaired)
@@ -60,6 +63,30 @@ def test_attention_core_any_width(mtf, case):
     for name, got, ref in (("dq", dq, dq_ref), ("dk", dk_, dk_ref), ("dv", dv, dv_ref)):
         err = m2(got.float().cpu().numpy(), ref.data)
         assert err <= TOL, (name, err)
+
+
+@pytest.mark.parametrize("dk", [128, 256])
+@pytest.mark.parametrize("scale", [-0.05, 0.0])
+def test_attention_core_negative_and_zero_scale(mtf, dk, scale):
+    """The kernels keep their running maximum on scale * logit with the scale's sign moved into an
+    operand; a zero scale makes every visible logit equal."""
+    b, l, h = 2, 100, 2
+    q, k, v, dctx = (mtf_inputs.normal(52, i, (b, l, h, dk)) for i in range(4))
+    qn, kn, vn = to_nt(q, (B, L, H, K)), to_nt(k, (B, M, H, K)), to_nt(v, (B, M, H, V))
+    ctx_ref, lse_ref = OL.attention_core_fwd(qn, kn, vn, scale, True)
+    ctx, lse = mtf.attention_fwd(q.cuda(), k.cuda(), v.cuda(), scale, True)
+    assert m2(ctx.float().cpu().numpy(), ctx_ref.data) <= TOL
+    assert np.max(np.abs(lse.cpu().numpy() - lse_ref.data)) <= 1e-3 * max(1.0, np.max(np.abs(lse_ref.data)))
+    ctx_s = torch.from_numpy(ctx_ref.data).to(torch.bfloat16)
+    lse_s = torch.from_numpy(lse_ref.data).float()
+    refs = OL.attention_core_bwd(qn, kn, vn, to_nt(ctx_s, (B, L, H, V)), to_nt(lse_s, (B, H, L)),
+                                 to_nt(dctx, (B, L, H, V)), scale, True)
+    gots = mtf.attention_bwd(q.cuda(), k.cuda(), v.cuda(), ctx_s.cuda(), lse_s.cuda(), dctx.cuda(), scale, True)
+    for name, got, ref in zip(("dq", "dk", "dv"), gots, refs):
+        if scale == 0.0 and name != "dv":       # dq = dk = 0 exactly: nothing to scale an error by
+            assert float(got.float().abs().max()) == 0.0, name
+        else:
+            assert m2(got.float().cpu().numpy(), ref.data) <= TOL, name
 
 
 def test_attention_core_errors(mtf):

@@ -109,6 +109,12 @@ def test_mha_single_position_and_one_tile_edge():
     _mha_case(mtf_inputs.mha_inputs(24, 1, 65, 64, 1, 128, 1), True, "length 65")
 
 
+def test_mha_head_width_256():
+    """The head width of the paper's language models through the same entry point: ragged, both masks."""
+    for causal in (False, True):
+        _mha_case(mtf_inputs.mha_inputs(27, 2, 168, 264, 3, 256, 24), causal, "x[2,168,264] 3 heads of width 256")
+
+
 def test_mha_config3_full_size():
     cfg = mtf_inputs.config3()
     _mha_case(cfg, cfg["causal"], "config 3", exact_gate=True)
@@ -176,6 +182,10 @@ def _layer_case(cfg, causal, label, exact_gate=False):
 
 def test_layer_small_ragged():
     _layer_case(mtf_inputs.layer_inputs(26, 2, 136, 256, 2, 128, 520, 64, 16384), True, "x[2,136,256]")
+
+
+def test_layer_head_width_256():
+    _layer_case(mtf_inputs.layer_inputs(28, 2, 200, 256, 2, 256, 520, 32, 16384), True, "x[2,200,256] 2 heads of width 256")
 
 
 def test_layer_config5_full_size():
