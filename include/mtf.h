@@ -341,7 +341,9 @@ int mtf_ffn_bias_bwd(const mtf_ffn_dims* d, const void* x, const void* a, const 
 
 /* Self-attention over x (memory = x).  logits = scale * q.k over d_k; softmax over the memory
  * positions; causal != 0 hides memory positions m > l.  Outputs q,k,v,ctx [batch,length,heads,
- * d_k] bf16 and lse [batch,heads,length] fp32 are saved for backward; y_partial fp32. */
+ * d_k] bf16 and lse [batch,heads,length] fp32 are saved for backward; y_partial fp32.
+ * d_k must be 128 or 256 (the head widths of the paper's experiments, which have fused attention
+ * kernels); another width is MTF_ERR_UNSUPPORTED here and served by mtf_attention_fwd / _bwd. */
 int mtf_mha_fwd(const mtf_mha_dims* d, const void* x, const void* w_q, const void* w_k,
                 const void* w_v, const void* w_o, float scale, int causal, void* q, void* k,
                 void* v, void* ctx, void* lse, void* y_partial, void* stream);
@@ -356,9 +358,10 @@ int mtf_mha_bwd(const mtf_mha_dims* d, const void* x, const void* w_q, const voi
 /* The attention core alone, for any head width d_k = d_v divisible by 8 (the LM models of the
  * paper use 256): ctx[batch,length,heads,d_k] = einsum(softmax_m(scale * einsum(q, k -> [batch,
  * heads,length,memory])), v), lse[batch,heads,length] fp32; q, k, v, ctx, dctx, dq, dk, dv bf16
- * [batch,length,heads,d_k].  d_k = 128 runs the fused kernels (no workspace forward); any other
- * width runs the two einsums on the GEMM kernel with a row-softmax kernel between them and needs
- * length % 8 == 0 and a workspace for the [batch,heads,length,length] intermediates.
+ * [batch,length,heads,d_k].  d_k = 128 and d_k = 256 run the fused kernels (no workspace forward,
+ * one fp32 per (batch, head, position) backward); any other width runs the two einsums on the GEMM
+ * kernel with a row-softmax kernel between them and needs length % 8 == 0 and a workspace for the
+ * [batch,heads,length,length] intermediates.
  * d->d_model is not used.  Errors: NULL, SIZE_MISMATCH, UNSUPPORTED, ALIGN, WORKSPACE, HIP. */
 size_t mtf_attention_fwd_workspace_bytes(const mtf_mha_dims* d);
 int mtf_attention_fwd(const mtf_mha_dims* d, const void* q, const void* k, const void* v,

@@ -157,13 +157,16 @@ def test_argument_validation_needs_no_gpu():
     assert lib.mtf_reduce_local(p, C.byref(big), p, C.byref(small), 0, 0, 0, None, C.c_size_t(0), None) == -11
     assert lib.mtf_reduce_local_workspace_bytes(C.byref(big), C.byref(small)) > 0
     # attention core at any head width
-    m256 = mtf.mtf_mha_dims(2, 16, 512, 2, 256)
-    assert lib.mtf_attention_fwd_workspace_bytes(C.byref(m256)) > 0
-    assert lib.mtf_attention_fwd_workspace_bytes(C.byref(mtf.mtf_mha_dims(2, 16, 256, 2, 128))) == 0    # fused
-    assert lib.mtf_attention_fwd(C.byref(m256), p, p, p, C.c_float(1.0), 0, p, p, None, C.c_size_t(0), None) == -11
-    assert lib.mtf_attention_fwd(C.byref(mtf.mtf_mha_dims(2, 12, 512, 2, 256)), p, p, p, C.c_float(1.0), 0, p, p,
+    m64 = mtf.mtf_mha_dims(2, 16, 128, 2, 64)                                 # no fused kernel at this width
+    assert lib.mtf_attention_fwd_workspace_bytes(C.byref(m64)) > 0
+    for fused in (128, 256):
+        mf = mtf.mtf_mha_dims(2, 16, 2 * fused, 2, fused)
+        assert lib.mtf_attention_fwd_workspace_bytes(C.byref(mf)) == 0
+        assert lib.mtf_attention_bwd_workspace_bytes(C.byref(mf)) == 2 * 2 * 16 * 4   # delta[batch, heads, length] fp32
+    assert lib.mtf_attention_fwd(C.byref(m64), p, p, p, C.c_float(1.0), 0, p, p, None, C.c_size_t(0), None) == -11
+    assert lib.mtf_attention_fwd(C.byref(mtf.mtf_mha_dims(2, 12, 128, 2, 64)), p, p, p, C.c_float(1.0), 0, p, p,
                                  p, C.c_size_t(1 << 30), None) == -10                                  # length % 8
-    assert lib.mtf_attention_bwd(C.byref(m256), p, p, p, p, p, None, C.c_float(1.0), 0, p, p, p, p,
+    assert lib.mtf_attention_bwd(C.byref(m64), p, p, p, p, p, None, C.c_float(1.0), 0, p, p, p, p,
                                  C.c_size_t(1 << 30), None) == -1
     # vocabulary-split operations
     i64 = C.c_int64
