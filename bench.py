@@ -6,6 +6,7 @@ backward of a full Transformer-layer shard (attention + feed-forward sublayers w
 residual adds), every contraction in the library's HIP kernels.  Prints ONE JSON line.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload layer|ffn|ffn_bias|mha|mesh|mesh3d|attention_lm|vocab|reshape]
+  python bench.py --workload ceiling|copy      (measurement aids, see below)
 
 `--workload copy` is not a benchmark of the path: it launches the library's plain copy kernel
 (fp32 -> fp32 cast) on a buffer of known size, which is what the HBM counters of a profiler run
@@ -23,6 +24,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA, published
+PEAK_HBM_GBS = 8000.0          # MI355X HBM3E, published
 METRIC = "TFLOP/s per-shard Transformer einsum (bf16) + % of MFMA peak on 1 MI355X"
 
 
@@ -41,7 +43,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="layer", choices=["layer", "ffn", "ffn_bias", "mha", "mesh", "mesh3d", "attention_lm", "vocab", "reshape", "copy"])
+    ap.add_argument("--workload", default="layer", choices=["layer", "ffn", "ffn_bias", "mha", "mesh", "mesh3d", "attention_lm", "vocab", "reshape", "copy", "ceiling"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--graph", action="store_true",
                     help="time replays of one captured HIP graph of the step instead of eager launches")
@@ -65,6 +67,8 @@ def main():
         return copy_calibration(args, torch, mtf, dev)
     if args.workload == "reshape":
         return reshape_bench(args, torch, mtf, mtf_inputs, dev)
+    if args.workload == "ceiling":
+        return ceiling_probe(args, torch, mtf, mtf_inputs, dev)
 
     # ---------------------------------------------------------------- workload
     if args.workload == "layer":
@@ -265,7 +269,7 @@ def main():
     kinds = mtf.timing_collect()
     # what the matrix cores alone sustain here, operands distributed like the path's (N(0,1) bf16)
     ops = mtf_inputs.normal(0, 99, (4096,)).to(torch.bfloat16).to(dev)
-    sink = torch.empty(64, dtype=torch.float32, device=dev)
+    sink = torch.empty(66, dtype=torch.float32, device=dev)
     for _ in range(12):                  # ~0.6 ms each: long enough for the clock to settle
         mtf.mfma_ceiling(ops, 2000, sink)
     ceil = [r for r in mtf.timing_collect() if r["kernel"] == "mfma_ceiling_kernel"]
@@ -275,9 +279,16 @@ def main():
     dom = kinds[0]
     avg_ms = dom["total_ms"] / dom["launches"]
     achieved = dom["flops"] / dom["launches"] / (avg_ms * 1e-3) / 1e12
-    roofline = dict(bound="mfma", achieved=round(achieved, 1), peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
-                    frac=round(achieved / PEAK_BF16_TFLOPS, 4),
-                    traffic=measured_traffic(args.workload, dom["kernel"]),
+    if dom["flops"] > 0:
+        roofline = dict(bound="mfma", achieved=round(achieved, 1), peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
+                        frac=round(achieved / PEAK_BF16_TFLOPS, 4))
+    else:                            # a step whose longest-running kernel moves bytes and multiplies nothing
+        gbs = dom["bytes"] / dom["launches"] / (avg_ms * 1e-3) / 1e9
+        roofline = dict(bound="hbm", achieved=round(gbs, 1), peak=PEAK_HBM_GBS, unit="GB/s",
+                        frac=round(gbs / PEAK_HBM_GBS, 4))
+    roofline.update(traffic=profile_field("dominant_kernel_hbm_traffic.txt", args.workload, dom["kernel"],
+                                          "traffic_bytes_per_launch"),
+                    mfma_busy=profile_field("layer_config5_counters.txt", args.workload, dom["kernel"], "mfma_busy"),
                     kernel=dom["kernel"], launches_per_step=dom["launches"] // args.steps,
                     avg_launch_us=round(avg_ms * 1e3, 2), mfma_only_measured_tflops=mfma_only)
     all_ms = sum(r["total_ms"] for r in kinds)
@@ -379,20 +390,50 @@ def reshape_bench(args, torch, mtf, mtf_inputs, dev):
     return 0 if ok else 1
 
 
-def measured_traffic(workload, kernel):
-    """HBM bytes per launch of `kernel`, from the committed rocprofv3 --pmc summary (FETCH_SIZE and
-    WRITE_SIZE runs scaled by the same counters on the copy kernel), or None if that summary is
-    for another kernel or workload."""
-    path = os.path.join(ROOT, "profiles", "dominant_kernel_hbm_traffic.txt")
+def ceiling_probe(args, torch, mtf, mtf_inputs, dev):
+    """What the matrix cores alone sustain (no memory traffic at all), by operand content: the
+    power a matrix instruction draws, hence the clock the chip holds, depends on the operand bits.
+    Not a benchmark of the path: the evidence behind roofline.mfma_only_measured_tflops."""
+    sink = torch.empty(66, dtype=torch.float32, device=dev)
+    out = {}
+    for label, ops in (("normal", mtf_inputs.normal(0, 99, (4096,)).to(torch.bfloat16)),
+                       ("ones", torch.ones(4096, dtype=torch.bfloat16)),
+                       ("zeros", torch.zeros(4096, dtype=torch.bfloat16))):
+        ops = ops.to(dev)
+        for _ in range(max(args.warmup, 1)):
+            mtf.mfma_ceiling(ops, 2000, sink)
+        torch.cuda.synchronize()
+        mtf.timing_enable(True)
+        mhz = []
+        for _ in range(args.steps):
+            mtf.mfma_ceiling(ops, 2000, sink)
+            cyc, ticks = sink[64:66].tolist()               # synchronises: one launch at a time
+            mhz.append(100.0 * cyc / ticks)
+        r = [k for k in mtf.timing_collect() if k["kernel"] == "mfma_ceiling_kernel"][0]
+        mtf.timing_enable(False)
+        out[label] = dict(tflops=round(r["flops"] / (r["total_ms"] * 1e-3) / 1e12, 1),
+                          avg_launch_us=round(r["total_ms"] * 1e3 / r["launches"], 1),
+                          shader_mhz_mean=round(sum(mhz) / len(mhz), 0), shader_mhz_min=round(min(mhz), 0))
+    print(json.dumps({"workload": "MFMA-only kernel (v_mfma_f32_32x32x16_bf16, 8 waves per CU, no memory traffic)",
+                      "peak_tflops_published": PEAK_BF16_TFLOPS, "operands": out}))
+    return 0
+
+
+def profile_field(filename, workload, kernel, key):
+    """A figure of `kernel` from a committed rocprofv3 --pmc summary under profiles/ (HBM bytes per
+    launch: FETCH_SIZE and WRITE_SIZE runs scaled by the same counters on the copy kernel; fraction
+    of time the matrix pipe is busy: the profiler's MfmaUtil), or None if that summary is for
+    another kernel or workload."""
+    path = os.path.join(ROOT, "profiles", filename)
     try:
         fields = {}
         for line in open(path):
             if "=" in line and not line.lstrip().startswith("#"):
                 k, v = line.split("=", 1)
-                fields[k.strip()] = v.strip()
+                fields.setdefault(k.strip(), v.strip())
         if fields.get("workload") != workload or fields.get("kernel") != kernel:
             return None
-        return float(fields["traffic_bytes_per_launch"])
+        return float(fields[key])
     except (OSError, KeyError, ValueError):
         return None
 

@@ -419,9 +419,11 @@ int mtf_timing_collect(mtf_kernel_time* out, int32_t max_kinds, int32_t* n_kinds
  * accumulators per wavefront, 8 wavefronts per CU on every CU), operands taken from `operands`
  * (device, bf16, at least 4096 elements; power draw, hence the sustained clock, depends on the
  * operand bits: pass values distributed like the real operands).  `iters` MFMAs per accumulator
- * (> 0).  `sink` (device, at least 64 floats) receives a value derived from the accumulators so
- * the loop is not optimised away.  *flops receives the FLOP of the launch (host).  Time it with
- * events or with mtf_timing_*: kernel name "mfma_ceiling_kernel". */
+ * (> 0).  `sink` (device, at least 66 floats): sink[0..63] receive a value derived from the
+ * accumulators so the loop is not optimised away; sink[64] and sink[65] the span of the first
+ * wavefront's loop in shader-clock cycles and in ticks of the constant 100 MHz clock (their ratio
+ * x 100 MHz is the clock the matrix cores were running at).  *flops receives the FLOP of the
+ * launch (host).  Time it with events or with mtf_timing_*: kernel name "mfma_ceiling_kernel". */
 int mtf_mfma_ceiling(const void* operands, int32_t iters, void* sink, double* flops, void* stream);
 
 #ifdef __cplusplus

@@ -578,7 +578,10 @@ class mtf_kernel_time(C.Structure):
 
 
 def mfma_ceiling(operands, iters, sink):
-    """One launch of the MFMA-only kernel; returns the FLOP it performs."""
+    """One launch of the MFMA-only kernel; returns the FLOP it performs.  sink: >= 66 floats
+    (sink[64], sink[65]: the loop's span in shader cycles and in 100 MHz ticks)."""
+    if operands.numel() < 4096 or sink.numel() < 66:
+        raise ValueError("mfma_ceiling: operands needs 4096 bf16 elements, sink 66 floats")
     flops = C.c_double()
     _check(lib.mtf_mfma_ceiling(_ptr(operands), C.c_int32(iters), _ptr(sink), C.byref(flops), _stream()))
     return flops.value
