@@ -14,6 +14,8 @@ Modules
   layer    feed-forward and multi-head-attention sublayers of the model-parallel
            Transformer (section 'Model-Parallel "Transformer"'), forward and backward,
            written as sequences of the named einsum
+  norm     layer normalisation over d_model (two reductions + component-wise operations),
+           forward and backward, alone and after the residual sum
   metrics  the error measures the parity tests gate on
 
 Pins (see tests/test_oracle_*.py): brute-force loops on tiny inputs, closed forms
@@ -22,7 +24,8 @@ paper prints (worked example and Table 1), the layout-independence statement of 
 worked example, Appendix B's two ratios, finite differences and the adjoint identity for
 every backward function, closed forms of softmax attention; the error measures of metrics by
 hand-computed vectors; the library-backed large-size einsum path against the written-out
-definition at sizes where the library re-orders the contraction.
+definition at sizes where the library re-orders the contraction; layer normalisation by values
+worked by hand, closed forms, its shift / scale invariance and finite differences.
 
 Parity unpinned: the layer *semantics* relative to the authors' own Transformer code
 (attention scale, mask constant, absence of layer norm / dropout / bias).  The paper
