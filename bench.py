@@ -5,7 +5,7 @@ One step = one pass of the whole hot path over one batch of synthetic input: for
 backward of a full Transformer-layer shard (attention + feed-forward sublayers with their
 residual adds), every contraction in the library's HIP kernels.  Prints ONE JSON line.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload layer|ffn|ffn_bias|mha|mesh|mesh3d|attention_lm|vocab|reshape]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload layer|ffn|ffn_bias|mha|mesh|mesh3d|attention_lm|vocab|reshape|layer_norm]
   python bench.py --workload ceiling|copy      (measurement aids, see below)
 
 `--workload copy` is not a benchmark of the path: it launches the library's plain copy kernel
@@ -43,7 +43,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="layer", choices=["layer", "ffn", "ffn_bias", "mha", "mesh", "mesh3d", "attention_lm", "vocab", "reshape", "copy", "ceiling"])
+    ap.add_argument("--workload", default="layer", choices=["layer", "ffn", "ffn_bias", "mha", "mesh", "mesh3d", "attention_lm", "vocab", "reshape", "layer_norm", "copy", "ceiling"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--graph", action="store_true",
                     help="time replays of one captured HIP graph of the step instead of eager launches")
@@ -67,6 +67,8 @@ def main():
         return copy_calibration(args, torch, mtf, dev)
     if args.workload == "reshape":
         return reshape_bench(args, torch, mtf, mtf_inputs, dev)
+    if args.workload == "layer_norm":
+        return layer_norm_bench(args, torch, mtf, mtf_inputs, dev)
     if args.workload == "ceiling":
         return ceiling_probe(args, torch, mtf, mtf_inputs, dev)
 
@@ -388,6 +390,53 @@ def reshape_bench(args, torch, mtf, mtf_inputs, dev):
                                    "avg_launch_us": round(kern["total_ms"] * 1e3 / kern["launches"], 2)},
                       "bit_exact": ok}))
     return 0 if ok else 1
+
+
+def layer_norm_bench(args, torch, mtf, mtf_inputs, dev):
+    """Layer normalisation at the layer shard's activation size (config 5: 8 x 512 tokens, d_model
+    1024): a step = the pass that adds two fp32 partial sums to the residual and normalises the
+    stored sum, and the backward pass.  HBM-bound: algorithmic bytes per step against 8 TB/s."""
+    b, l, d = 8, 512, 1024
+    x = mtf_inputs.normal(9, 0, (b, l, d)).to(dev)
+    dy = mtf_inputs.normal(9, 1, (b, l, d)).to(dev)
+    gain = (mtf_inputs.normal(9, 2, (d,), 0.25, torch.float32) + 1.0).to(torch.bfloat16).to(dev)
+    bias = mtf_inputs.normal(9, 3, (d,), 0.5).to(dev)
+    parts = [mtf_inputs.normal(9, 4 + i, (b, l, d), 0.7, torch.float32).to(dev) for i in range(2)]
+
+    def step():
+        u, y, mean, rstd = mtf.residual_layer_norm_fwd(parts, x, gain, bias, 1e-6)
+        return mtf.layer_norm_bwd(u, gain, mean, rstd, dy)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    gc.collect()
+    gc.disable()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / args.steps
+    gc.enable()
+    mtf.timing_enable(True)
+    for _ in range(args.steps):
+        step()
+    kinds = {r["kernel"]: r for r in mtf.timing_collect()}
+    mtf.timing_enable(False)
+    nbytes = sum(r["bytes"] for r in kinds.values()) / args.steps
+    dom = kinds["layer_norm_fwd_kernel"]
+    gbs = dom["bytes"] / (dom["total_ms"] * 1e-3) / 1e9
+    print(json.dumps({"metric": "layer normalisation after the residual sum, forward + backward, HBM-bound",
+                      "value": round(nbytes / dt / 1e9, 1), "unit": "GB/s", "ms_per_step": round(dt * 1e3, 4),
+                      "bytes_per_step": nbytes, "steps": args.steps, "warmup": args.warmup, "dtype": "bf16",
+                      "config": {"workload": f"residual[{b},{l},{d}] + 2 fp32 partial sums -> layer norm; backward"},
+                      "roofline": {"bound": "hbm", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                                   "frac": round(gbs / PEAK_HBM_GBS, 4), "kernel": "layer_norm_fwd_kernel",
+                                   "avg_launch_us": round(dom["total_ms"] * 1e3 / dom["launches"], 2)},
+                      "kernels": {k: dict(us_per_step=round(r["total_ms"] * 1e3 / args.steps, 1),
+                                          gbs=round(r["bytes"] / (r["total_ms"] * 1e-3) / 1e9, 1))
+                                  for k, r in kinds.items()}}))
+    return 0
 
 
 def ceiling_probe(args, torch, mtf, mtf_inputs, dev):

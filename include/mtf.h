@@ -249,6 +249,40 @@ int mtf_reduce_local_static(const void* in, const mtf_shape* in_local, void* out
                             const mtf_shape* out_local, mtf_dtype in_dt, mtf_dtype out_dt,
                             mtf_reduce_op op, void* stream);
 
+/* ---------------------------------------------------------------- device: layer normalisation
+ * The paper's Transformer is the original one, where every sublayer output is normalised:
+ * LayerNorm(x + Sublayer(x)).  In the paper's terms (section "Operation Implementation") that is
+ * two reductions over d_model (paragraph "Reduction": the mean, then the mean squared deviation)
+ * and component-wise operations with implicit broadcasting (paragraph "Component-wise
+ * Operations"): y = gain * (x - mean) / sqrt(var + eps) + bias, biased variance, statistics in
+ * fp32.  d_model must be unsplit (both reductions local), a multiple of 8 and at most 4096.
+ * x, y, dy, dx, u: device bf16 [rows, d_model] row-major (rows = product of the other dims);
+ * gain, bias: device bf16 [d_model]; mean, rstd = 1/sqrt(var + eps): device fp32 [rows], saved for
+ * the backward; dgain, dbias: device fp32 [d_model].  eps >= 0.
+ * Errors: NULL, SIZE_MISMATCH, UNSUPPORTED, ALIGN, WORKSPACE, HIP. */
+int mtf_layer_norm_fwd(const void* x, const void* gain, const void* bias, float eps, int64_t rows,
+                       int64_t d_model, void* y, void* mean, void* rstd, void* stream);
+
+/* The same as the tail of the pass that completes a sublayer: u = residual + sum of n (1..4) fp32
+ * partial sums [rows, d_model] (what the Allreduce of a one-slice group and the residual add
+ * deliver; added in the order residual, partial 0, 1, ...; u stored bf16), then the
+ * normalisation of the STORED u: one pass over the data instead of mtf_reduce_partials followed
+ * by mtf_layer_norm_fwd, with bit-identical u, y and statistics. */
+int mtf_residual_layer_norm_fwd(const void* const* partials, int32_t n, const void* residual,
+                                const void* gain, const void* bias, float eps, int64_t rows,
+                                int64_t d_model, void* u, void* y, void* mean, void* rstd,
+                                void* stream);
+
+/* Gradients of sum(y * dy): dx = rstd * (g - mean_d(g) - xhat * mean_d(g * xhat)) with
+ * xhat = (x - mean) * rstd, g = gain * dy; dgain = sum over rows of dy * xhat, dbias = sum over
+ * rows of dy (fixed summation order: reproducible run to run).  x is the tensor that was
+ * normalised (u of the residual form).  workspace: device scratch of
+ * mtf_layer_norm_bwd_workspace_bytes() (column partials per workgroup). */
+size_t mtf_layer_norm_bwd_workspace_bytes(int64_t rows, int64_t d_model);
+int mtf_layer_norm_bwd(const void* x, const void* gain, const void* mean, const void* rstd,
+                       const void* dy, int64_t rows, int64_t d_model, void* dx, void* dgain,
+                       void* dbias, void* workspace, size_t workspace_bytes, void* stream);
+
 /* ---------------------------------------------------------------- device: vocabulary-split operations
  * Section 'Model-Parallel "Transformer"': vocab is split across the mesh like d_ff and heads.
  * The paper gives no formulas for the operations that carry vocab; they are taken as its own

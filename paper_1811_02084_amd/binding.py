@@ -571,6 +571,59 @@ def layer_bwd(x, w, saved, dz, scale, causal, bufs):
     return bufs["dx"]
 
 
+# ------------------------------------------------------------------ layer normalisation
+def _bf16_rows(t, what):
+    if t.dtype != torch.bfloat16:
+        raise ValueError(f"{what} must be bf16")
+    d = t.shape[-1]
+    return t.numel() // d if d else 0, d
+
+
+def layer_norm_fwd(x, gain, bias, eps):
+    """x bf16 [..., d_model], gain / bias bf16 [d_model] -> (y bf16, mean fp32 [...], rstd fp32 [...])."""
+    rows, d = _bf16_rows(x, "x")
+    y = torch.empty_like(x)
+    mean = torch.empty(x.shape[:-1], dtype=torch.float32, device=x.device)
+    rstd = torch.empty_like(mean)
+    lib.mtf_layer_norm_fwd.argtypes = [C.c_void_p] * 3 + [C.c_float, C.c_int64, C.c_int64] + [C.c_void_p] * 4
+    _check(lib.mtf_layer_norm_fwd(_ptr(x), _ptr(gain), _ptr(bias), eps, rows, d, _ptr(y), _ptr(mean), _ptr(rstd),
+                                  _stream()))
+    return y, mean, rstd
+
+
+def residual_layer_norm_fwd(partials, residual, gain, bias, eps):
+    """u = residual + sum(partials) stored bf16, then the normalisation of u -> (u, y, mean, rstd)."""
+    rows, d = _bf16_rows(residual, "residual")
+    n = len(partials)
+    for p_ in partials:
+        if p_.dtype != torch.float32 or p_.shape != residual.shape or not p_.is_contiguous():
+            raise ValueError("partials must be contiguous fp32 tensors of the residual's shape")
+    arr = (C.c_void_p * max(n, 1))(*[p_.data_ptr() for p_ in partials])
+    u, y = torch.empty_like(residual), torch.empty_like(residual)
+    mean = torch.empty(residual.shape[:-1], dtype=torch.float32, device=residual.device)
+    rstd = torch.empty_like(mean)
+    lib.mtf_residual_layer_norm_fwd.argtypes = ([C.c_void_p, C.c_int32] + [C.c_void_p] * 3 +
+                                                [C.c_float, C.c_int64, C.c_int64] + [C.c_void_p] * 5)
+    _check(lib.mtf_residual_layer_norm_fwd(arr, n, _ptr(residual), _ptr(gain), _ptr(bias), eps, rows, d,
+                                           _ptr(u), _ptr(y), _ptr(mean), _ptr(rstd), _stream()))
+    return u, y, mean, rstd
+
+
+def layer_norm_bwd(x, gain, mean, rstd, dy):
+    """-> (dx bf16, dgain fp32 [d_model], dbias fp32 [d_model])."""
+    rows, d = _bf16_rows(x, "x")
+    dx = torch.empty_like(x)
+    dgain = torch.empty(d, dtype=torch.float32, device=x.device)
+    dbias = torch.empty_like(dgain)
+    lib.mtf_layer_norm_bwd_workspace_bytes.restype = C.c_size_t
+    lib.mtf_layer_norm_bwd_workspace_bytes.argtypes = [C.c_int64, C.c_int64]
+    ws = _ws(lib.mtf_layer_norm_bwd_workspace_bytes(rows, d), x.device)
+    lib.mtf_layer_norm_bwd.argtypes = [C.c_void_p] * 5 + [C.c_int64, C.c_int64] + [C.c_void_p] * 4 + [C.c_size_t, C.c_void_p]
+    _check(lib.mtf_layer_norm_bwd(_ptr(x), _ptr(gain), _ptr(mean), _ptr(rstd), _ptr(dy), rows, d, _ptr(dx),
+                                  _ptr(dgain), _ptr(dbias), _ptr(ws), ws.numel(), _stream()))
+    return dx, dgain, dbias
+
+
 # ------------------------------------------------------------------ measurement aid
 class mtf_kernel_time(C.Structure):
     _fields_ = [("kernel", C.c_char * 96), ("launches", C.c_int64), ("total_ms", C.c_double),

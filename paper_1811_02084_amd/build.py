@@ -10,7 +10,7 @@ LIB = os.path.join(HERE, "libmtf.so")
 
 SOURCES = ["mtf_host.cpp", "elementwise.hip", "einsum_local.hip", "gemm_bf16.hip", "gemm_bf16_large.hip", "gemm_bf16_small.hip", "gemm_bf16_small_deep.hip",
            "gemm_bf16_split.hip",
-           "attention.hip", "attention_unfused.hip", "layer.hip", "timing.hip", "broadcast_reduce.hip", "vocab.hip", "reshape.hip"]
+           "attention.hip", "attention_unfused.hip", "layer.hip", "timing.hip", "broadcast_reduce.hip", "vocab.hip", "reshape.hip", "layer_norm.hip"]
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wno-inline-asm",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",   # see README: no packed fp32

@@ -168,8 +168,22 @@ def test_argument_validation_needs_no_gpu():
                                  p, C.c_size_t(1 << 30), None) == -10                                  # length % 8
     assert lib.mtf_attention_bwd(C.byref(m64), p, p, p, p, p, None, C.c_float(1.0), 0, p, p, p, p,
                                  C.c_size_t(1 << 30), None) == -1
-    # vocabulary-split operations
+    # layer normalisation
     i64 = C.c_int64
+    lib.mtf_layer_norm_bwd_workspace_bytes.restype = C.c_size_t
+    assert lib.mtf_layer_norm_fwd(None, p, p, C.c_float(1e-6), i64(4), i64(64), p, p, p, None) == -1
+    assert lib.mtf_layer_norm_fwd(p, p, p, C.c_float(1e-6), i64(4), i64(60), p, p, p, None) == -10      # d_model % 8
+    assert lib.mtf_layer_norm_fwd(p, p, p, C.c_float(1e-6), i64(4), i64(8192), p, p, p, None) == -10    # too wide
+    assert lib.mtf_layer_norm_fwd(p, p, p, C.c_float(1e-6), i64(-1), i64(64), p, p, p, None) == -3
+    assert lib.mtf_layer_norm_fwd(p, p, p, C.c_float(1e-6), i64(0), i64(64), p, p, p, None) == 0        # no rows
+    assert lib.mtf_layer_norm_fwd(C.c_void_p(4100), p, p, C.c_float(1e-6), i64(4), i64(64), p, p, p, None) == -14
+    assert lib.mtf_residual_layer_norm_fwd(None, 0, p, p, p, C.c_float(1e-6), i64(4), i64(64), p, p, p, p, None) == -10
+    assert lib.mtf_residual_layer_norm_fwd(None, 2, p, p, p, C.c_float(1e-6), i64(4), i64(64), p, p, p, p, None) == -1
+    assert lib.mtf_layer_norm_bwd_workspace_bytes(i64(4096), i64(1024)) == 512 * 2 * 1024 * 4
+    assert lib.mtf_layer_norm_bwd_workspace_bytes(i64(6), i64(64)) == 2 * 2 * 64 * 4
+    assert lib.mtf_layer_norm_bwd(p, p, p, p, p, i64(8), i64(64), p, p, p, None, C.c_size_t(0), None) == -11
+    assert lib.mtf_layer_norm_bwd(p, p, p, p, p, i64(8), i64(64), p, None, p, p, C.c_size_t(1 << 20), None) == -1
+    # vocabulary-split operations
     assert lib.mtf_embedding_local(None, i64(4), p, i64(8), i64(16), i64(0), p, 0, None) == -1
     assert lib.mtf_embedding_local(p, i64(4), p, i64(8), i64(12), i64(0), p, 0, None) == -10          # d_model % 8
     assert lib.mtf_embedding_local(p, i64(0), None, i64(8), i64(16), i64(0), None, 0, None) == 0      # no tokens
