@@ -272,3 +272,59 @@ def lowered_reshape(t, out_dims, mesh, layout):
             n = mesh[axis][1]
             cur = {c: np.array_split(cur[c], n, axis=pos_out[axis][0])[c[axis]] for c in all_coords(mesh)}
     return {c: NT(np.array(a, order="C"), tuple(out_dims)) for c, a in cur.items()}
+
+
+# ----------------------------------------------------------------------------- reshape that changes sizes
+
+def reshape_general(t, out_dims, out_sizes, mesh, layout):
+    """A reshape that may change rank and dim sizes (subsection "Reshape": "simple in the
+    non-distributed case"): the elements keep their row-major order, the output gets its own
+    names and is laid out by them.  This is the definition: reshape the full tensor, then slice.
+    Returns dict coord -> NT."""
+    total = 1
+    for n in out_sizes:
+        total *= n
+    if len(out_dims) != len(out_sizes) or total != t.data.size:
+        raise LayoutError("SIZE_MISMATCH", f"{t.data.shape} -> {tuple(out_sizes)}")
+    full = NT(np.array(t.data, order="C").reshape(tuple(out_sizes)), tuple(out_dims))
+    return {c: slice_tensor(full, mesh, layout, c) for c in all_coords(mesh)}
+
+
+def lowered_reshape_general(t, out_dims, out_sizes, mesh, layout):
+    """The same from the processors' INPUT slices, one element at a time: an element of a
+    processor's output slice has a position in the full output, hence a row-major rank among all
+    elements, hence a position in the full input; the input slice that holds that position belongs
+    to the processor whose coordinate on every mesh axis that splits an input dim is the stripe
+    the position falls in (on the other axes: the reader's own coordinate - those processors hold
+    copies).  Plain loops; for small cases.  Returns dict coord -> NT."""
+    in_dims, in_sizes = t.dims, t.data.shape
+    lin = tensor_layout(in_dims, mesh, layout)
+    slices = {c: slice_tensor(t, mesh, layout, c) for c in all_coords(mesh)}
+    total = 1
+    for n in out_sizes:
+        total *= n
+    if len(out_dims) != len(out_sizes) or total != t.data.size:
+        raise LayoutError("SIZE_MISMATCH", f"{in_sizes} -> {tuple(out_sizes)}")
+    result = {}
+    for c in all_coords(mesh):
+        offs, locs = slice_spec(out_dims, out_sizes, mesh, layout, c)
+        out = np.empty(locs, dtype=np.float64)
+        for idx in np.ndindex(*locs):
+            rank = 0                                    # row-major rank of the element in the full tensor
+            for i, n in enumerate(out_sizes):
+                rank = rank * n + offs[i] + idx[i]
+            pos = [0] * len(in_sizes)                   # its position in the full input
+            for i in range(len(in_sizes) - 1, -1, -1):
+                pos[i] = rank % in_sizes[i]
+                rank //= in_sizes[i]
+            owner, local = list(c), []
+            for i, d in enumerate(in_dims):
+                if d in lin:
+                    stripe = in_sizes[i] // mesh[lin[d]][1]
+                    owner[lin[d]] = pos[i] // stripe
+                    local.append(pos[i] % stripe)
+                else:
+                    local.append(pos[i])
+            out[idx] = slices[tuple(owner)].data[tuple(local)]
+        result[c] = NT(out, tuple(out_dims))
+    return result
