@@ -210,6 +210,18 @@ int mtf_reshape_plan(const mtf_shape* in, const mtf_shape* out, const mtf_place*
 int mtf_reshape_virtual(const void* const* in_slices, const mtf_shape* in, const mtf_shape* out,
                         const mtf_place* p, void* out_slice, mtf_dtype dt, void* stream);
 
+/* A reshape that changes rank or dim sizes (subsection "Reshape", first sentence: simple in the
+ * non-distributed case, communication in the distributed one): the elements keep their row-major
+ * order, `out` (GLOBAL shape, same number of elements as `in`, its own names) is laid out by its
+ * names.  Same arguments and conventions as mtf_reshape_virtual; an element of the output slice is
+ * fetched from the input slice of the processor whose coordinates are the stripes the element's
+ * position in `in` falls in (this processor's own coordinates on mesh dims that split no dim of
+ * `in`).  The paper names no collective for this case; on the virtual mesh it is a gather.
+ * Bit-exact.  Errors: those of mtf_slice for either shape; SIZE_MISMATCH if the element counts
+ * differ; RANK for a rank-0 shape; UNSUPPORTED above 64 processors. */
+int mtf_reshape_general_virtual(const void* const* in_slices, const mtf_shape* in, const mtf_shape* out,
+                                const mtf_place* p, void* out_slice, mtf_dtype dt, void* stream);
+
 /* ---------------------------------------------------------------- device: component-wise addition
  * Section "Mesh-TensorFlow syntax": out = a + b where b's dims are a subset of a's (any order);
  * b is repeated along the dims it lacks.  out has a's shape.  Section "Operation

@@ -286,6 +286,12 @@ def reshape_general(t, out_dims, out_sizes, mesh, layout):
         total *= n
     if len(out_dims) != len(out_sizes) or total != t.data.size:
         raise LayoutError("SIZE_MISMATCH", f"{t.data.shape} -> {tuple(out_sizes)}")
+    # both views must be legal under the layout (names first, then divisibility, as reshape_plan)
+    tensor_layout(t.dims, mesh, layout)
+    tensor_layout(tuple(out_dims), mesh, layout)
+    origin = (0,) * len(mesh)
+    slice_spec(t.dims, t.data.shape, mesh, layout, origin)
+    slice_spec(out_dims, out_sizes, mesh, layout, origin)
     full = NT(np.array(t.data, order="C").reshape(tuple(out_sizes)), tuple(out_dims))
     return {c: slice_tensor(full, mesh, layout, c) for c in all_coords(mesh)}
 

@@ -237,6 +237,23 @@ def reshape_virtual(in_slices, in_shape, out_shape, mesh, layout, coord, out=Non
     return out
 
 
+def reshape_general_virtual(in_slices, in_shape, out_shape, mesh, layout, coord, out=None):
+    """reshape_virtual for a reshape that changes rank or sizes (row-major element order kept)."""
+    k = _Keep()
+    si, so = k.shape(in_shape), k.shape(out_shape)
+    p = k.place(mesh, layout, coord)
+    if out is None:
+        _, sz = slice(out_shape, mesh, layout, coord)
+        out = torch.empty(sz, dtype=in_slices[0].dtype, device=in_slices[0].device)
+    arr = (C.c_void_p * len(in_slices))(*[t.data_ptr() for t in in_slices])
+    for t in in_slices:
+        if not t.is_cuda or not t.is_contiguous():
+            raise ValueError("slices must be contiguous device tensors")
+    _check(lib.mtf_reshape_general_virtual(arr, C.byref(si), C.byref(so), C.byref(p), _ptr(out), _dt(out),
+                                           _stream()))
+    return out
+
+
 # ------------------------------------------------------------------ device calls
 def slice_copy(full, dims, mesh, layout, coord, slice_buf=None, scatter=False):
     """Gathers the slice of `full` (scatter=False) or writes slice_buf back into it."""

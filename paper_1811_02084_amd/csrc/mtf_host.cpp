@@ -147,6 +147,34 @@ int reshape_info(const Dims& in, const Dims& out, const mtf_place* p, bool need_
   return MTF_OK;
 }
 
+int reshape_general_info(const Dims& in, const Dims& out, const mtf_place* p, GeneralReshapeInfo* r) {
+  int64_t n_in = 1, n_out = 1;
+  for (int i = 0; i < in.rank; ++i) n_in *= in.size[i];
+  for (int i = 0; i < out.rank; ++i) n_out *= out.size[i];
+  if (n_in != n_out)
+    return fail(MTF_ERR_SIZE_MISMATCH, "reshape changes the number of elements (%lld -> %lld)", (long long)n_in,
+                (long long)n_out);
+  Place pl;
+  if (int rc = load_place(p, false, &pl)) return rc;
+  int out_axis[MTF_MAX_RANK];
+  if (int rc = restrict_layout(in, pl, r->in_axis)) return rc;
+  if (int rc = restrict_layout(out, pl, out_axis)) return rc;
+  if (int rc = check_coord(p, &pl)) return rc;
+  int64_t in_off[MTF_MAX_RANK];
+  if (int rc = stripes(in, pl, r->in_axis, in_off, r->in_local)) return rc;
+  if (int rc = stripes(out, pl, out_axis, r->out_offset, r->out_local)) return rc;
+  r->in_rank = in.rank;
+  r->out_rank = out.rank;
+  for (int i = 0; i < in.rank; ++i) r->in_size[i] = in.size[i];
+  for (int i = 0; i < out.rank; ++i) r->out_size[i] = out.size[i];
+  r->mesh_rank = pl.mesh.rank;
+  for (int m = 0; m < pl.mesh.rank; ++m) {
+    r->mesh_size[m] = pl.mesh.size[m];
+    r->coord[m] = p->coord[m];
+  }
+  return MTF_OK;
+}
+
 // ------------------------------------------------------------------------- canonical einsum
 static bool mergeable(const Loop& outer, const Loop& inner) {
   // outer/inner adjacent in every tensor that has them: outer stride = inner stride * extent

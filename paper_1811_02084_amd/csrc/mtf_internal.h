@@ -43,6 +43,17 @@ struct ReshapeInfo {
 // need_coord: also validate p->coord and fill out_offset / coord (else they are 0).
 int reshape_info(const Dims& in, const Dims& out, const mtf_place* p, bool need_coord, ReshapeInfo* r);
 
+// A reshape that may change rank and sizes (the elements keep their row-major order): what the
+// processor at p->coord holds of the output, and how any processor's input slice is cut.
+struct GeneralReshapeInfo {
+  int in_rank, out_rank, mesh_rank;
+  int64_t mesh_size[MTF_MAX_RANK], coord[MTF_MAX_RANK];
+  int in_axis[MTF_MAX_RANK];
+  int64_t in_size[MTF_MAX_RANK], in_local[MTF_MAX_RANK];
+  int64_t out_size[MTF_MAX_RANK], out_local[MTF_MAX_RANK], out_offset[MTF_MAX_RANK];
+};
+int reshape_general_info(const Dims& in, const Dims& out, const mtf_place* p, GeneralReshapeInfo* r);
+
 // ---------------------------------------------------------------------------------------------
 // Canonical form of a two-operand named einsum for the device kernels.
 //

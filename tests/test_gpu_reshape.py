@@ -98,3 +98,100 @@ def test_seeded_sweep_of_reshapes(mtf):
             assert np.array_equal(got.double().cpu().numpy(), want[c].data), (case, c)
         done += 1
     assert done >= 20
+
+
+# ------------------------------------------------------------------ reshape that changes rank / sizes
+from oracle.layout import LayoutError, reshape_general  # noqa: E402
+
+GENERAL = [  # mesh, layout, in dims, in sizes, out dims, out sizes
+    ([("x", 2)], [("a", "x"), ("d", "x")], ("a", "b"), (4, 6), ("c", "d"), (3, 8)),
+    # [batch, length, hidden] -> [tokens, heads, k]: splitting heads out of the hidden dim, as an
+    # attention layer does, with batch split before and heads after
+    ([("x", 2), ("y", 4)], [("batch", "x"), ("heads", "y")], ("batch", "length", "hidden"), (4, 48, 1024),
+     ("tokens", "heads", "k"), (192, 8, 128)),
+    # and back: heads merged into hidden, tokens split into [batch, length]
+    ([("x", 2), ("y", 4)], [("batch", "x"), ("heads", "y")], ("tokens", "heads", "k"), (192, 8, 128),
+     ("batch", "length", "hidden"), (4, 48, 1024)),
+    ([("x", 2), ("y", 2)], [("tokens", "x"), ("hidden", "y")], ("tokens", "heads", "k"), (8, 4, 3),
+     ("batch", "length", "hidden"), (2, 4, 12)),                                  # odd innermost: scalar runs
+    ([("x", 4)], [("p", "x"), ("s", "x")], ("p", "q", "r"), (4, 2, 6), ("s", "t"), (8, 6)),
+    ([("x", 3)], [("nothing", "x")], ("a", "b"), (5, 7), ("c",), (35,)),
+    ([("x", 2), ("y", 2)], [("a", "x"), ("b", "y"), ("c", "y"), ("d", "x")], ("a", "b"), (64, 48), ("c", "d"), (48, 64)),
+    ([("x", 4)], [("flat", "x")], ("a", "b", "c", "d", "e"), (2, 3, 4, 5, 8), ("flat",), (960,)),
+]
+
+
+@pytest.mark.parametrize("case", GENERAL, ids=[f"{'x'.join(map(str, c[3]))}->{'x'.join(map(str, c[5]))}" for c in GENERAL])
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_reshape_general_virtual(mtf, case, dtype):
+    mesh, layout, in_dims, in_sizes, out_dims, out_sizes = case
+    t = mtf_inputs.normal(42, len(in_sizes), in_sizes, dtype=dtype)
+    want = reshape_general(nt(t.double().numpy(), in_dims), out_dims, out_sizes, mesh, layout)
+    in_shape, out_shape = list(zip(in_dims, in_sizes)), list(zip(out_dims, out_sizes))
+    full = t.cuda()
+    coords = all_coords(mesh)
+    slices = [None] * len(coords)
+    for c in coords:
+        slices[coord_to_rank(mesh, c)] = mtf.slice_copy(full, in_dims, mesh, layout, c)
+    for c in coords:
+        got = mtf.reshape_general_virtual(slices, in_shape, out_shape, mesh, layout, c)
+        assert got.shape == want[c].data.shape
+        assert np.array_equal(got.double().cpu().numpy(), want[c].data), c
+
+
+def test_reshape_general_errors_and_equal_sizes(mtf):
+    x = torch.zeros(24, device="cuda")
+    with pytest.raises(mtf.MtfError) as e:
+        mtf.reshape_general_virtual([x, x], [("a", 4), ("b", 6)], [("c", 5), ("d", 5)], [("all", 2)], [], (0,))
+    assert e.value.name == "MTF_ERR_SIZE_MISMATCH"
+    with pytest.raises(mtf.MtfError) as e:
+        mtf.reshape_general_virtual([x, x], [("a", 4), ("b", 6)], [("c", 8), ("d", 3)], [("all", 2)], [("d", "all")], (0,))
+    assert e.value.name == "MTF_ERR_INDIVISIBLE"
+    # with equal sizes it is the renaming reshape
+    mesh, layout = [("all", 4)], [("batch", "all"), ("hidden", "all")]
+    t = mtf_inputs.normal(42, 9, (64, 256)).cuda()
+    slices = [mtf.slice_copy(t, ("batch", "units"), mesh, layout, (c,)) for c in range(4)]
+    shape_in, shape_out = [("batch", 64), ("units", 256)], [("examples", 64), ("hidden", 256)]
+    for c in range(4):
+        a = mtf.reshape_virtual(slices, shape_in, shape_out, mesh, layout, (c,))
+        b = mtf.reshape_general_virtual(slices, shape_in, shape_out, mesh, layout, (c,))
+        assert torch.equal(a, b)
+
+
+def test_seeded_sweep_of_size_changing_reshapes(mtf):
+    """Random factorizations of one element count on two meshes: what the oracle accepts must come
+    out bit-exact on every processor; what it rejects the library must reject with the same code."""
+    rng = np.random.Generator(np.random.Philox(key=[mtf_inputs.BASE_SEED, 72]))
+    meshes = [([("all", 4)], [("batch", "all"), ("hidden", "all"), ("vocab", "all")]),
+              ([("rows", 2), ("cols", 3)], [("batch", "rows"), ("hidden", "cols"), ("vocab", "cols"), ("z", "rows")])]
+    pool = ["batch", "hidden", "vocab", "z", "a", "b", "c", "d"]
+    shapes = [(24, 36), (864,), (12, 72), (6, 4, 36), (36, 24), (2, 12, 36), (8, 108), (3, 3, 96), (4, 6, 6, 6)]
+    done = 0
+    for case in range(150):
+        mesh, layout = meshes[case % 2]
+        in_sizes = shapes[int(rng.integers(len(shapes)))]
+        out_sizes = shapes[int(rng.integers(len(shapes)))]
+        in_dims = tuple(rng.choice(pool, size=len(in_sizes), replace=False))
+        out_dims = tuple(rng.choice(pool, size=len(out_sizes), replace=False))
+        in_shape, out_shape = list(zip(in_dims, in_sizes)), list(zip(out_dims, out_sizes))
+        t = mtf_inputs.normal(43, case, in_sizes, dtype=torch.float32)
+        coords = all_coords(mesh)
+        try:
+            want = reshape_general(nt(t.double().numpy(), in_dims), out_dims, out_sizes, mesh, layout)
+        except LayoutError as err:
+            with pytest.raises(mtf.MtfError) as e:
+                # (an output buffer is passed so that the binding does not size one, which would
+                # look at the output shape alone first)
+                mtf.reshape_general_virtual([t.cuda()] * len(coords), in_shape, out_shape, mesh, layout, coords[0],
+                                            out=torch.empty(864, device="cuda"))
+            assert e.value.name == "MTF_ERR_" + err.code, (case, err.code)
+            continue
+        full = t.cuda()
+        slices = [None] * len(coords)
+        for c in coords:
+            slices[coord_to_rank(mesh, c)] = mtf.slice_copy(full, in_dims, mesh, layout, c)
+        for c in coords:
+            got = mtf.reshape_general_virtual(slices, in_shape, out_shape, mesh, layout, c)
+            assert np.array_equal(got.double().cpu().numpy(), want[c].data), (case, c)
+        done += 1
+    assert done >= 40
