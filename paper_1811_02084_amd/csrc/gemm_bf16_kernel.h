@@ -301,6 +301,7 @@ __global__ void __launch_bounds__(Cfg::kThreads, Cfg::kWavesPerSimd) gemm_bf16_k
   // a further tile.
   constexpr int kAhead = Cfg::kFragAhead;
   constexpr int kSteps = Cfg::kSteps;
+  constexpr bool kStaggerIssue = Cfg::kWaves == 8 && Cfg::kWavesPerSimd == 2;
   static_assert(kSteps % (kAhead + 1) == 0, "fragment buffers must rotate back at a tile boundary");
   static_assert(kAhead < kSteps, "fetch-ahead of at most one k-tile");
   bf16x8 af[kAhead + 1][TM], bf[kAhead + 1][TN];
@@ -350,9 +351,14 @@ __global__ void __launch_bounds__(Cfg::kThreads, Cfg::kWavesPerSimd) gemm_bf16_k
     for (int ks = 0; ks < kSteps; ++ks) {
       const int cur = ks % (kAhead + 1), nxt = (ks + kAhead) % (kAhead + 1);
       const bool crosses = ks + kAhead >= kSteps;  // the fetch of this step reads the next tile
+      // The two waves of a SIMD (w and w + 4) pass the barrier together; were both to issue their
+      // loads of the further tile right away, the matrix pipe would idle meanwhile.  The second
+      // one does this step's MFMAs first (any time after the barrier is safe for the stage, and
+      // the loads have a whole k-tile to land).
+      const bool issue_late = kStaggerIssue && wave >= 4;
       if (HAS_NEXT && ks + kAhead == kSteps) {
         wait_for_tile(kt + 1);
-        if (fill) issue_next(fill);
+        if (fill && !issue_late) issue_next(fill);
         __builtin_amdgcn_sched_barrier(0);
       }
 #pragma unroll
@@ -371,6 +377,10 @@ __global__ void __launch_bounds__(Cfg::kThreads, Cfg::kWavesPerSimd) gemm_bf16_k
           // before its first use (fewer live registers) and the overlap is lost
           __builtin_amdgcn_sched_barrier(0);
         }
+      if (HAS_NEXT && ks + kAhead == kSteps && fill && issue_late) {
+        issue_next(fill);
+        __builtin_amdgcn_sched_barrier(0);
+      }
     }
   };
 
