@@ -158,6 +158,13 @@ struct TileLoader {
     }
   }
 
+  // A tile that lies entirely inside K.
+  __device__ __forceinline__ void issue_full(const char* origin, char* tile, int wave) const {
+#pragma unroll
+    for (int i = 0; i < NL; ++i)
+      load16_to_lds(origin, off[i], lds_address(tile) + (i * NWAVES + wave) * 1024);
+  }
+
   // origin: address of element (mn0, k0) of the operand (wave-uniform).
   __device__ __forceinline__ void issue(const char* origin, char* tile, int wave, int lane,
                                         int k_left) const {
@@ -275,18 +282,27 @@ __global__ void __launch_bounds__(Cfg::kThreads, Cfg::kWavesPerSimd) gemm_bf16_k
   uint32_t full_hist = 0;                             // bit i: the (i+1)-th latest issued tile was full
 
   auto issue_next = [&](char* st) {
-    // skip exhausted (or empty) segments
+    // The common case first, under one branch: a full k-tile of the segment in progress.  (This
+    // runs once per k-tile in every wave, between MFMAs; the general path below is some hundred
+    // scalar instructions and a dozen branches.)
+    if (next_left >= BK) {
+      load_a.issue_full(next_a, st, wave);
+      load_b.issue_full(next_b, st + Cfg::kATile, wave);
+      full_hist = (full_hist << 1) | 1u;
+    } else {
+      // skip exhausted (or empty) segments
 #pragma unroll
-    for (int q = 0; q < kMaxSegments - 1; ++q)
-      if (next_left <= 0 && next_seg == q) {
-        next_seg = q + 1;
-        next_a = seg_a[q + 1];
-        next_b = seg_b[q + 1];
-        next_left = seg_k[q + 1];
-      }
-    load_a.issue(next_a, st, wave, lane, next_left);
-    load_b.issue(next_b, st + Cfg::kATile, wave, lane, next_left);
-    full_hist = (full_hist << 1) | (next_left >= BK ? 1u : 0u);
+      for (int q = 0; q < kMaxSegments - 1; ++q)
+        if (next_left <= 0 && next_seg == q) {
+          next_seg = q + 1;
+          next_a = seg_a[q + 1];
+          next_b = seg_b[q + 1];
+          next_left = seg_k[q + 1];
+        }
+      load_a.issue(next_a, st, wave, lane, next_left);
+      load_b.issue(next_b, st + Cfg::kATile, wave, lane, next_left);
+      full_hist = (full_hist << 1) | (next_left >= BK ? 1u : 0u);
+    }
     next_a += a_tile_bytes;
     next_b += b_tile_bytes;
     next_left -= BK;
