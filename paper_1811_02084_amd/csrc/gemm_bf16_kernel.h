@@ -434,14 +434,23 @@ __global__ void __launch_bounds__(Cfg::kThreads, Cfg::kWavesPerSimd) gemm_bf16_k
   // path) is requested one slab ahead, the first slab's before the barrier below - from clamped,
   // always valid addresses, so that the loads need no branch around them.
   auto my_slab = [&](int i) { return WK == 1 || (i / (TM / 2)) == kg; };
-  uint2 aux_v[2][8];
+  // Read-back shape: a lane handles kW consecutive columns of one row, 16 bytes of the output
+  // (4 fp32 or 8 bf16), so that every global access is 16 bytes per lane whatever the output type.
+  constexpr int kW = OUT_BF16 ? 8 : 4;          // columns per lane
+  constexpr int kLanesPerRow = 64 / kW;         // 16 or 8
+  constexpr int kRowsPerIt = 64 / kLanesPerRow; // rows a wave covers per instruction: 4 or 8
+  constexpr int kIts = 32 / kRowsPerIt;         // instructions per 32-row slab: 8 or 4
+  struct alignas(kW * 2) AuxVec {
+    uint32_t w[kW / 2];  // kW bf16 values
+  };
+  AuxVec aux_v[2][kIts];
   auto request_mask = [&](int i) {
-    const int out_row_ = lane >> 4, out_col_ = (lane & 15) * 4;
+    const int out_row_ = lane / kLanesPerRow, out_col_ = (lane % kLanesPerRow) * kW;
 #pragma unroll
-    for (int it = 0; it < 8; ++it) {
-      const int mc = min(m0 + wave_m + i * 32 + it * 4 + out_row_, M - 1);
-      const int nc = min(n0 + wave_n + out_col_, N - 4);  // N % 8 == 0
-      aux_v[i & 1][it] = *reinterpret_cast<const uint2*>(g.aux + offC + (int64_t)mc * ldc + nc);
+    for (int it = 0; it < kIts; ++it) {
+      const int mc = min(m0 + wave_m + i * 32 + it * kRowsPerIt + out_row_, M - 1);
+      const int nc = min(n0 + wave_n + out_col_, N - kW);  // N % 8 == 0
+      aux_v[i & 1][it] = *reinterpret_cast<const AuxVec*>(g.aux + offC + (int64_t)mc * ldc + nc);
     }
   };
   if (EPI == MTF_EPI_MASK_GT0) {
@@ -501,16 +510,19 @@ __global__ void __launch_bounds__(Cfg::kThreads, Cfg::kWavesPerSimd) gemm_bf16_k
   static_assert(Cfg::kWaves * 32 * kPitch <= NS * Cfg::kStage, "slab area fits the ring");
   char* slab = ring + wave * (32 * kPitch);
   const int lane_m = lane & 31, lane_h = lane >> 5;
-  const int out_row = lane >> 4, out_col = (lane & 15) * 4;  // read-back: 4 rows per instruction
+  const int out_row = lane / kLanesPerRow, out_col = (lane % kLanesPerRow) * kW;
   void* const Cg = g.C[grp];
-  // a lane reads back the same 4 columns of every slab: its bias values are loaded once
-  float bias4[4] = {0.f, 0.f, 0.f, 0.f};
+  // a lane reads back the same kW columns of every slab: its bias values are loaded once
+  float biasv[kW];
+#pragma unroll
+  for (int e = 0; e < kW; ++e) biasv[e] = 0.f;
   if (g.bias && n0 + wave_n + out_col < N) {
-    const uint2 b2 = *reinterpret_cast<const uint2*>(g.bias + n0 + wave_n + out_col);
-    bias4[0] = __uint_as_float(b2.x << 16);
-    bias4[1] = __uint_as_float(b2.x & 0xffff0000u);
-    bias4[2] = __uint_as_float(b2.y << 16);
-    bias4[3] = __uint_as_float(b2.y & 0xffff0000u);
+#pragma unroll
+    for (int e = 0; e < kW; e += 2) {
+      const uint32_t b2 = *reinterpret_cast<const uint32_t*>(g.bias + n0 + wave_n + out_col + e);
+      biasv[e] = __uint_as_float(b2 << 16);
+      biasv[e + 1] = __uint_as_float(b2 & 0xffff0000u);
+    }
   }
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
@@ -519,20 +531,18 @@ __global__ void __launch_bounds__(Cfg::kThreads, Cfg::kWavesPerSimd) gemm_bf16_k
     // The old C of an accumulating store is requested for the whole slab before anything waits on
     // it (clamped addresses again): one memory round trip per slab, hidden behind the slab's pass
     // through LDS, instead of one per row group.
-    uint2 old_bf[8];
-    float4 old_f[8];
+    AuxVec old_bf[kIts];
+    float4 old_f[kIts];
     if (g.accumulate) {
 #pragma unroll
-      for (int it = 0; it < 8; ++it) {
-        const int mc = min(m0 + wave_m + i * 32 + it * 4 + out_row, M - 1);
-        const int nc = min(n0 + wave_n + out_col, N - 4);  // N % 8 == 0
+      for (int it = 0; it < kIts; ++it) {
+        const int mc = min(m0 + wave_m + i * 32 + it * kRowsPerIt + out_row, M - 1);
+        const int nc = min(n0 + wave_n + out_col, N - kW);  // N % 8 == 0
         const int64_t idc = offC + (int64_t)mc * ldc + nc;
-        {
-          if (OUT_BF16)
-            old_bf[it] = *reinterpret_cast<const uint2*>(static_cast<const bf16_t*>(Cg) + idc);
-          else
-            old_f[it] = *reinterpret_cast<const float4*>(static_cast<const float*>(Cg) + idc);
-        }
+        if (OUT_BF16)
+          old_bf[it] = *reinterpret_cast<const AuxVec*>(static_cast<const bf16_t*>(Cg) + idc);
+        else
+          old_f[it] = *reinterpret_cast<const float4*>(static_cast<const float*>(Cg) + idc);
       }
     }
 #pragma unroll
@@ -546,25 +556,31 @@ __global__ void __launch_bounds__(Cfg::kThreads, Cfg::kWavesPerSimd) gemm_bf16_k
       }
     __builtin_amdgcn_wave_barrier();
 #pragma unroll
-    for (int it = 0; it < 8; ++it) {
-      const int r = it * 4 + out_row;
-      const f32x4 t = *LDS_PTR(const f32x4, slab + r * kPitch + out_col * 4);
+    for (int it = 0; it < kIts; ++it) {
+      const int r = it * kRowsPerIt + out_row;
+      float v[kW];
+#pragma unroll
+      for (int h4 = 0; h4 < kW / 4; ++h4) {
+        const f32x4 t = *LDS_PTR(const f32x4, slab + r * kPitch + (out_col + h4 * 4) * 4);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[h4 * 4 + e] = t[e];
+      }
       const int m = m0 + wave_m + i * 32 + r;
       const int n = n0 + wave_n + out_col;
       if (m >= M || n >= N) continue;
       const int64_t idx = offC + (int64_t)m * ldc + n;
-      float v[4] = {t[0], t[1], t[2], t[3]};
       if (g.row_scale) {
         const float rs = g.row_scale[(int64_t)zb * M + m];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) v[e] *= rs;
+        for (int e = 0; e < kW; ++e) v[e] *= rs;
       }
       if (g.accumulate) {
         if (OUT_BF16) {
-          v[0] += __uint_as_float(old_bf[it].x << 16);
-          v[1] += __uint_as_float(old_bf[it].x & 0xffff0000u);
-          v[2] += __uint_as_float(old_bf[it].y << 16);
-          v[3] += __uint_as_float(old_bf[it].y & 0xffff0000u);
+#pragma unroll
+          for (int e = 0; e < kW; e += 2) {
+            v[e] += __uint_as_float(old_bf[it].w[e / 2] << 16);
+            v[e + 1] += __uint_as_float(old_bf[it].w[e / 2] & 0xffff0000u);
+          }
         } else {
           v[0] += old_f[it].x;
           v[1] += old_f[it].y;
@@ -573,22 +589,27 @@ __global__ void __launch_bounds__(Cfg::kThreads, Cfg::kWavesPerSimd) gemm_bf16_k
         }
       }
 #pragma unroll
-      for (int e = 0; e < 4; ++e) v[e] += bias4[e];
+      for (int e = 0; e < kW; ++e) v[e] += biasv[e];
       if (EPI == MTF_EPI_RELU) {
 #pragma unroll
-        for (int e = 0; e < 4; ++e) v[e] = fmaxf(v[e], 0.f);
+        for (int e = 0; e < kW; ++e) v[e] = fmaxf(v[e], 0.f);
       } else if (EPI == MTF_EPI_MASK_GT0) {
         // bf16 > 0  <=>  sign bit clear and magnitude non-zero
-        const uint2 mk = aux_v[i & 1][it];
-        const uint32_t w[4] = {mk.x & 0xffffu, mk.x >> 16, mk.y & 0xffffu, mk.y >> 16};
+        const AuxVec mk = aux_v[i & 1][it];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) v[e] = (w[e] != 0u && w[e] < 0x8000u) ? v[e] : 0.f;
+        for (int e = 0; e < kW; ++e) {
+          const uint32_t w = (e & 1) ? (mk.w[e / 2] >> 16) : (mk.w[e / 2] & 0xffffu);
+          v[e] = (w != 0u && w < 0x8000u) ? v[e] : 0.f;
+        }
       }
-      if (OUT_BF16)
-        *reinterpret_cast<uint2*>(static_cast<bf16_t*>(Cg) + idx) =
-            make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
-      else
+      if (OUT_BF16) {
+        AuxVec o;
+#pragma unroll
+        for (int e = 0; e < kW; e += 2) o.w[e / 2] = pack_bf16x2(v[e], v[e + 1]);
+        *reinterpret_cast<AuxVec*>(static_cast<bf16_t*>(Cg) + idx) = o;
+      } else {
         *reinterpret_cast<float4*>(static_cast<float*>(Cg) + idx) = make_float4(v[0], v[1], v[2], v[3]);
+      }
     }
     __builtin_amdgcn_wave_barrier();
   }
