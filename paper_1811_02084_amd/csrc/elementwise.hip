@@ -98,54 +98,62 @@ struct PartialPtrs {
 };
 
 // NFIX > 0: exactly NFIX partials, their loads unrolled so that all of a thread's requests are in
-// flight before the first addition; NFIX == 0: any n, one partial at a time.
+// flight before the first addition; NFIX == 0: any n, one partial at a time.  A thread handles 8
+// consecutive elements: two 16-byte loads per fp32 operand, one 16-byte access per bf16 operand.
 template <bool RES_BF16, bool OUT_BF16, int NFIX>
 __global__ void __launch_bounds__(256) reduce_partials_kernel(PartialPtrs parts, int n,
                                                              const void* __restrict__ residual,
                                                              void* __restrict__ out, int64_t count) {
-  const int64_t vecs = count / 4;
+  const int64_t vecs = count / 8;
   for (int64_t v = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; v < vecs;
        v += (int64_t)gridDim.x * blockDim.x) {
-    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-    float4 x[NFIX > 0 ? NFIX : 1];
-    if (NFIX > 0) {
-#pragma unroll
-      for (int i = 0; i < NFIX; ++i) x[i] = reinterpret_cast<const float4*>(parts.p[i])[v];
-    }
-    if (residual) {
-      if (RES_BF16) {
-        uint2 r = reinterpret_cast<const uint2*>(residual)[v];
-        acc = make_float4(__uint_as_float(r.x << 16), __uint_as_float(r.x & 0xffff0000u),
-                          __uint_as_float(r.y << 16), __uint_as_float(r.y & 0xffff0000u));
-      } else {
-        acc = reinterpret_cast<const float4*>(residual)[v];
-      }
-    }
-    // fixed order: residual, then partial 0, 1, ...
+    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    float4 x[NFIX > 0 ? NFIX : 1][2];
     if (NFIX > 0) {
 #pragma unroll
       for (int i = 0; i < NFIX; ++i) {
-        acc.x += x[i].x;
-        acc.y += x[i].y;
-        acc.z += x[i].z;
-        acc.w += x[i].w;
-      }
-    } else {
-      for (int i = 0; i < n; ++i) {
-        const float4 y = reinterpret_cast<const float4*>(parts.p[i])[v];
-        acc.x += y.x;
-        acc.y += y.y;
-        acc.z += y.z;
-        acc.w += y.w;
+        x[i][0] = reinterpret_cast<const float4*>(parts.p[i])[2 * v];
+        x[i][1] = reinterpret_cast<const float4*>(parts.p[i])[2 * v + 1];
       }
     }
-    if (OUT_BF16)
-      reinterpret_cast<uint2*>(out)[v] = make_uint2(pack_bf16x2(acc.x, acc.y), pack_bf16x2(acc.z, acc.w));
-    else
-      reinterpret_cast<float4*>(out)[v] = acc;
+    if (residual) {
+      if (RES_BF16) {
+        const uint4 r = reinterpret_cast<const uint4*>(residual)[v];
+        const uint32_t w[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          acc[2 * e] = __uint_as_float(w[e] << 16);
+          acc[2 * e + 1] = __uint_as_float(w[e] & 0xffff0000u);
+        }
+      } else {
+        const float4 lo = reinterpret_cast<const float4*>(residual)[2 * v];
+        const float4 hi = reinterpret_cast<const float4*>(residual)[2 * v + 1];
+        acc[0] = lo.x; acc[1] = lo.y; acc[2] = lo.z; acc[3] = lo.w;
+        acc[4] = hi.x; acc[5] = hi.y; acc[6] = hi.z; acc[7] = hi.w;
+      }
+    }
+    // fixed order: residual, then partial 0, 1, ...
+    auto add = [&](const float4& lo, const float4& hi) {
+      acc[0] += lo.x; acc[1] += lo.y; acc[2] += lo.z; acc[3] += lo.w;
+      acc[4] += hi.x; acc[5] += hi.y; acc[6] += hi.z; acc[7] += hi.w;
+    };
+    if (NFIX > 0) {
+#pragma unroll
+      for (int i = 0; i < NFIX; ++i) add(x[i][0], x[i][1]);
+    } else {
+      for (int i = 0; i < n; ++i)
+        add(reinterpret_cast<const float4*>(parts.p[i])[2 * v], reinterpret_cast<const float4*>(parts.p[i])[2 * v + 1]);
+    }
+    if (OUT_BF16) {
+      reinterpret_cast<uint4*>(out)[v] = make_uint4(pack_bf16x2(acc[0], acc[1]), pack_bf16x2(acc[2], acc[3]),
+                                                   pack_bf16x2(acc[4], acc[5]), pack_bf16x2(acc[6], acc[7]));
+    } else {
+      reinterpret_cast<float4*>(out)[2 * v] = make_float4(acc[0], acc[1], acc[2], acc[3]);
+      reinterpret_cast<float4*>(out)[2 * v + 1] = make_float4(acc[4], acc[5], acc[6], acc[7]);
+    }
   }
-  // ragged tail (count not a multiple of 4): one thread each
-  int64_t t = vecs * 4 + blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+  // ragged tail (count not a multiple of 8): one thread each
+  int64_t t = vecs * 8 + blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
   if (t < count) {
     float acc = 0.f;
     if (residual)
@@ -207,11 +215,11 @@ int mtf_reduce_partials(const void* const* partials, int32_t n, const void* resi
   }
   if (!aligned16(out) || !aligned16(residual)) return fail(MTF_ERR_ALIGN, "out / residual");
   hipStream_t s = static_cast<hipStream_t>(stream);
-  int blocks = (int)std::min<int64_t>(ceil_div(ceil_div(count, 4), 256), 256 * 8);
+  int blocks = (int)std::min<int64_t>(ceil_div(ceil_div(count, 8), 256), 256 * 8);
   bool rb = residual && residual_dt == MTF_BF16, ob = out_dt == MTF_BF16;
   LaunchTimer timer("reduce_partials_kernel", 0,
                     (double)count * (4.0 * n + (residual ? (rb ? 2 : 4) : 0) + (ob ? 2 : 4)), s);
-  // one vector per thread (count / 4 threads) up to 8 workgroups per CU, grid-stride beyond
+  // one vector per thread (count / 8 threads) up to 8 workgroups per CU, grid-stride beyond
   auto launch = [&](auto res_bf16, auto out_bf16) {
     constexpr bool RB = decltype(res_bf16)::value, OB = decltype(out_bf16)::value;
     switch (n) {
