@@ -13,7 +13,7 @@ SOURCES = ["mtf_host.cpp", "elementwise.hip", "einsum_local.hip", "gemm_bf16.hip
            "attention.hip", "attention_unfused.hip", "layer.hip", "timing.hip", "broadcast_reduce.hip", "vocab.hip", "reshape.hip", "layer_norm.hip"]
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wno-inline-asm",
-         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",   # see README: no packed fp32
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",   # no packed fp32 instructions (unreliable here)
          "-I", INCLUDE, "-I", CSRC]
 
 
