@@ -27,9 +27,10 @@
  *
  * Contents: slices and lowering plans (host); slice gather, the local einsum with its fused
  * epilogues, partial-sum reduce (the Allreduce stand-in on a virtual mesh); component-wise
- * addition with implicit broadcasting, local reductions; reshape on a virtual mesh; the
- * vocabulary-split operations; fixed steps of the model-parallel Transformer layer (feed-forward
- * with and without bias, attention core, multi-head attention, whole layer); measurement aids.
+ * addition with implicit broadcasting, local reductions; reshape on a virtual mesh (renaming,
+ * and changing rank or sizes); layer normalisation over d_model; the vocabulary-split operations;
+ * fixed steps of the model-parallel Transformer layer (feed-forward with and without bias,
+ * attention core at head widths 128 and 256, multi-head attention, whole layer); measurement aids.
  */
 #ifndef MTF_H_
 #define MTF_H_
