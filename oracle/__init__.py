@@ -16,6 +16,8 @@ Modules
            written as sequences of the named einsum
   norm     layer normalisation over d_model (two reductions + component-wise operations),
            forward and backward, alone and after the residual sum
+  optim    the step of synchronous data-parallel training with replicated parameters
+           (Algorithm 1): sum of the processors' gradients, gradient-descent update
   metrics  the error measures the parity tests gate on
 
 Pins (see tests/test_oracle_*.py): brute-force loops on tiny inputs, closed forms
@@ -25,7 +27,8 @@ worked example, Appendix B's two ratios, finite differences and the adjoint iden
 every backward function, closed forms of softmax attention; the error measures of metrics by
 hand-computed vectors; the library-backed large-size einsum path against the written-out
 definition at sizes where the library re-orders the contraction; layer normalisation by values
-worked by hand, closed forms, its shift / scale invariance and finite differences.
+worked by hand, closed forms, its shift / scale invariance and finite differences; the training
+step by hand-worked values and by the sub-batch gradients adding up to the batch gradient.
 
 Parity unpinned: the layer *semantics* relative to the authors' own Transformer code
 (attention scale, mask constant, absence of layer norm / dropout / bias).  The paper
