@@ -188,6 +188,19 @@ int mtf_reduce_partials(const void* const* partials, int32_t n, const void* resi
                         mtf_dtype residual_dt, void* out, mtf_dtype out_dt, int64_t count,
                         void* stream);
 
+/* ---------------------------------------------------------------- device: the data-parallel training step
+ * Section "Inspiration: Single-Program-Multiple-Data (SPMD) Batch-Splitting", Algorithm 1, steps
+ * 2 and 3 for one parameter tensor: the gradients the n processors of the data-parallel group
+ * computed on their sub-batches are summed (the Allreduce; on one GPU the sum of the virtual
+ * processors' buffers, in the fixed order 0, 1, ...) and the parameter is updated.  The paper
+ * leaves Update open: plain gradient descent, master <- master - lr * sum.
+ * grads: HOST array of n (1..64) DEVICE pointers to fp32 buffers of `count` elements; master:
+ * device fp32, in and out (the full-precision copy of the parameter); weights: device bf16, out,
+ * the rounded copy the einsums read (may be NULL).  Errors: NULL, UNSUPPORTED, SIZE_MISMATCH,
+ * ALIGN, HIP. */
+int mtf_sgd_step(const void* const* grads, int32_t n, float lr, void* master, void* weights,
+                 int64_t count, void* stream);
+
 /* ---------------------------------------------------------------- reshape (same sizes, new names)
  * Subsection "Reshape": keeping the dim sizes and changing dim names changes the layout, and
  * with it what each processor must hold.  `in` and `out` are GLOBAL shapes of equal rank and

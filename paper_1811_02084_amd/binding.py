@@ -326,6 +326,20 @@ def reduce_partials(partials, residual=None, out_dtype=torch.float32, out=None):
     return out
 
 
+def sgd_step(grads, lr, master, weights=None):
+    """master (fp32, in place) -= lr * sum(grads); weights (bf16, optional) <- rounded master."""
+    n, count = len(grads), master.numel()
+    for g_ in grads:
+        if g_.dtype != torch.float32 or g_.numel() != count or not g_.is_contiguous():
+            raise ValueError("gradients must be contiguous fp32 tensors of the parameter's size")
+    if master.dtype != torch.float32 or (weights is not None and (weights.dtype != torch.bfloat16 or weights.numel() != count)):
+        raise ValueError("master must be fp32, weights bf16 of the same size")
+    arr = (C.c_void_p * n)(*[g_.data_ptr() for g_ in grads])
+    lib.mtf_sgd_step.argtypes = [C.c_void_p, C.c_int32, C.c_float, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
+    _check(lib.mtf_sgd_step(arr, n, lr, _ptr(master), _ptr(weights), count, _stream()))
+    return master, weights
+
+
 def add_broadcast(a, a_dims, b, b_dims, out_dtype=None):
     """a + b with b's dims a subset of a's (b repeated along the dims it lacks)."""
     k = _Keep()

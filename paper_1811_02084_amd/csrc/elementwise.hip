@@ -167,6 +167,54 @@ __global__ void __launch_bounds__(256) reduce_partials_kernel(PartialPtrs parts,
   }
 }
 
+// W <- W - lr * (g_0 + g_1 + ...) on the fp32 master copy, summed in that fixed order; the bf16
+// copy the einsums read is written alongside.  8 elements per thread, 16-byte accesses.
+template <int NFIX>
+__global__ void __launch_bounds__(256) sgd_step_kernel(PartialPtrs grads, int n, float lr, float* __restrict__ master,
+                                                      bf16_t* __restrict__ weights, int64_t count) {
+  const int64_t vecs = count / 8;
+  for (int64_t v = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; v < vecs;
+       v += (int64_t)gridDim.x * blockDim.x) {
+    float4 x[NFIX > 0 ? NFIX : 1][2];
+    if (NFIX > 0) {
+#pragma unroll
+      for (int i = 0; i < NFIX; ++i) {
+        x[i][0] = reinterpret_cast<const float4*>(grads.p[i])[2 * v];
+        x[i][1] = reinterpret_cast<const float4*>(grads.p[i])[2 * v + 1];
+      }
+    }
+    const float4 m0 = reinterpret_cast<const float4*>(master)[2 * v];
+    const float4 m1 = reinterpret_cast<const float4*>(master)[2 * v + 1];
+    float sum[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    auto add = [&](const float4& lo, const float4& hi) {
+      sum[0] += lo.x; sum[1] += lo.y; sum[2] += lo.z; sum[3] += lo.w;
+      sum[4] += hi.x; sum[5] += hi.y; sum[6] += hi.z; sum[7] += hi.w;
+    };
+    if (NFIX > 0) {
+#pragma unroll
+      for (int i = 0; i < NFIX; ++i) add(x[i][0], x[i][1]);
+    } else {
+      for (int i = 0; i < n; ++i)
+        add(reinterpret_cast<const float4*>(grads.p[i])[2 * v], reinterpret_cast<const float4*>(grads.p[i])[2 * v + 1]);
+    }
+    const float w[8] = {m0.x - lr * sum[0], m0.y - lr * sum[1], m0.z - lr * sum[2], m0.w - lr * sum[3],
+                        m1.x - lr * sum[4], m1.y - lr * sum[5], m1.z - lr * sum[6], m1.w - lr * sum[7]};
+    reinterpret_cast<float4*>(master)[2 * v] = make_float4(w[0], w[1], w[2], w[3]);
+    reinterpret_cast<float4*>(master)[2 * v + 1] = make_float4(w[4], w[5], w[6], w[7]);
+    if (weights)
+      reinterpret_cast<uint4*>(weights)[v] = make_uint4(pack_bf16x2(w[0], w[1]), pack_bf16x2(w[2], w[3]),
+                                                       pack_bf16x2(w[4], w[5]), pack_bf16x2(w[6], w[7]));
+  }
+  int64_t t = vecs * 8 + blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+  if (t < count) {
+    float sum = 0.f;
+    for (int i = 0; i < n; ++i) sum += grads.p[i][t];
+    const float w = master[t] - lr * sum;
+    master[t] = w;
+    if (weights) weights[t] = f32_to_bf16(w);
+  }
+}
+
 template <bool IN_BF16, bool OUT_BF16>
 __global__ void __launch_bounds__(256) cast_kernel(const void* __restrict__ in, void* __restrict__ out,
                                                   int64_t count) {
@@ -239,6 +287,34 @@ int mtf_reduce_partials(const void* const* partials, int32_t n, const void* resi
   else
     launch(std::false_type{}, std::false_type{});
   return launch_status("reduce_partials_kernel");
+}
+
+int mtf_sgd_step(const void* const* grads, int32_t n, float lr, void* master, void* weights,
+                 int64_t count, void* stream) {
+  if (!grads) return fail(MTF_ERR_NULL, "grads");
+  if (n < 1 || n > 64) return fail(MTF_ERR_UNSUPPORTED, "%d gradient buffers (1..64)", n);
+  if (count < 0) return fail(MTF_ERR_SIZE_MISMATCH, "count %lld", (long long)count);
+  if (count == 0) return MTF_OK;
+  if (!master) return fail(MTF_ERR_NULL, "master");
+  PartialPtrs pp;
+  for (int i = 0; i < n; ++i) {
+    if (!grads[i]) return fail(MTF_ERR_NULL, "gradient %d", i);
+    if (!aligned16(grads[i])) return fail(MTF_ERR_ALIGN, "gradient %d", i);
+    pp.p[i] = static_cast<const float*>(grads[i]);
+  }
+  if (!aligned16(master) || !aligned16(weights)) return fail(MTF_ERR_ALIGN, "master / weights");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const int blocks = (int)std::min<int64_t>(ceil_div(ceil_div(count, 8), 256), 256 * 8);
+  LaunchTimer timer("sgd_step_kernel", 0, (double)count * (4.0 * n + 8.0 + (weights ? 2.0 : 0.0)), s);
+  float* m = static_cast<float*>(master);
+  bf16_t* w = static_cast<bf16_t*>(weights);
+  switch (n) {
+    case 1: sgd_step_kernel<1><<<blocks, 256, 0, s>>>(pp, n, lr, m, w, count); break;
+    case 2: sgd_step_kernel<2><<<blocks, 256, 0, s>>>(pp, n, lr, m, w, count); break;
+    case 4: sgd_step_kernel<4><<<blocks, 256, 0, s>>>(pp, n, lr, m, w, count); break;
+    default: sgd_step_kernel<0><<<blocks, 256, 0, s>>>(pp, n, lr, m, w, count); break;
+  }
+  return launch_status("sgd_step_kernel");
 }
 
 int mtf_cast(const void* in, mtf_dtype in_dt, void* out, mtf_dtype out_dt, int64_t count,

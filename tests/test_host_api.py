@@ -168,6 +168,13 @@ def test_argument_validation_needs_no_gpu():
                                  p, C.c_size_t(1 << 30), None) == -10                                  # length % 8
     assert lib.mtf_attention_bwd(C.byref(m64), p, p, p, p, p, None, C.c_float(1.0), 0, p, p, p, p,
                                  C.c_size_t(1 << 30), None) == -1
+    # the data-parallel training step
+    arr1 = (C.c_void_p * 1)(4096)
+    assert lib.mtf_sgd_step(None, 1, C.c_float(0.1), p, p, C.c_int64(8), None) == -1
+    assert lib.mtf_sgd_step(arr1, 0, C.c_float(0.1), p, p, C.c_int64(8), None) == -10
+    assert lib.mtf_sgd_step(arr1, 1, C.c_float(0.1), None, p, C.c_int64(8), None) == -1
+    assert lib.mtf_sgd_step(arr1, 1, C.c_float(0.1), C.c_void_p(4100), p, C.c_int64(8), None) == -14
+    assert lib.mtf_sgd_step(arr1, 1, C.c_float(0.1), None, None, C.c_int64(0), None) == 0       # nothing to update
     # layer normalisation
     i64 = C.c_int64
     lib.mtf_layer_norm_bwd_workspace_bytes.restype = C.c_size_t
