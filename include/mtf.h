@@ -26,7 +26,8 @@
  *     machine without one.
  *
  * Contents: slices and lowering plans (host); slice gather, the local einsum with its fused
- * epilogues, partial-sum reduce (the Allreduce stand-in on a virtual mesh); component-wise
+ * epilogues, partial-sum reduce (the Allreduce stand-in on a virtual mesh), the data-parallel
+ * training step; component-wise
  * addition with implicit broadcasting, local reductions; reshape on a virtual mesh (renaming,
  * and changing rank or sizes); layer normalisation over d_model; the vocabulary-split operations;
  * fixed steps of the model-parallel Transformer layer (feed-forward with and without bias,
