@@ -8,6 +8,7 @@ namespace mtf {
 
 constexpr int kMaxSegments = 3;
 constexpr int kMaxGroup = 4;
+constexpr int kMaxSlots = 8;  // (A, B, K) triples of one launch: problems x segments per problem
 
 // C[z][m][n] (+)= alpha * sum_s sum_k A_s[z][m][k] * B_s[z][k][n], then the epilogue.
 //
@@ -41,12 +42,14 @@ struct GemmDesc {
   int64_t sA0 = 0, sA1 = 0, sB0 = 0, sB1 = 0, sC0 = 0, sC1 = 0;
   // Grouped launch: up to kMaxGroup - 1 further independent problems with the same operand
   // layouts, epilogue (NONE only), output dtype and alpha run in the same launch, so that several
-  // small outputs fill the machine together.  Requires nseg == 1, no batch, no accumulate.
+  // small outputs fill the machine together.  Every problem of the group has `nseg` segments
+  // ((1 + nextra) * nseg <= kMaxSlots; a segment may have K = 0).  No batch, no accumulate.
   struct Extra {
-    const bf16_t* A = nullptr;
-    const bf16_t* B = nullptr;
+    const bf16_t* A[kMaxSegments] = {nullptr, nullptr, nullptr};
+    const bf16_t* B[kMaxSegments] = {nullptr, nullptr, nullptr};
+    int64_t K[kMaxSegments] = {0, 0, 0};
     void* C = nullptr;
-    int64_t M = 0, N = 0, K = 0, lda = 0, ldb = 0, ldc = 0;
+    int64_t M = 0, N = 0, lda = 0, ldb = 0, ldc = 0;
   };
   int nextra = 0;
   Extra extra[kMaxGroup - 1];

@@ -38,14 +38,19 @@ bool gemm_bf16_supported(const GemmDesc& d) {
   if (d.row_scale && d.nextra > 0) return false;
   if (d.batch0 * d.batch1 > 65535) return false;
   if (d.nextra < 0 || d.nextra > kMaxGroup - 1) return false;
-  if (d.nextra > 0 && (d.nseg != 1 || d.batch0 * d.batch1 != 1 || d.accumulate || d.epi != MTF_EPI_NONE))
+  if (d.nextra > 0 && ((1 + d.nextra) * d.nseg > kMaxSlots || d.batch0 * d.batch1 != 1 || d.accumulate ||
+                       d.epi != MTF_EPI_NONE))
     return false;
   for (int p = 0; p < d.nextra; ++p) {
     const GemmDesc::Extra& e = d.extra[p];
-    if (e.M <= 0 || e.N <= 0 || e.K < 0 || e.M > INT32_MAX || e.N > INT32_MAX || e.K > INT32_MAX) return false;
+    if (e.M <= 0 || e.N <= 0 || e.M > INT32_MAX || e.N > INT32_MAX) return false;
     if (e.lda % 8 || e.ldb % 8 || e.ldc % 4 || e.N % 8 || (!d.a_kcontig && e.M % 8)) return false;
-    if ((d.a_kcontig || d.b_kcontig) && e.K % 8) return false;
-    if (!e.A || !e.B || !e.C || !aligned16(e.A) || !aligned16(e.B) || !aligned16(e.C)) return false;
+    for (int s = 0; s < d.nseg; ++s) {
+      if (e.K[s] < 0 || e.K[s] > INT32_MAX) return false;
+      if ((d.a_kcontig || d.b_kcontig) && e.K[s] % 8) return false;
+      if (!e.A[s] || !e.B[s] || !aligned16(e.A[s]) || !aligned16(e.B[s])) return false;
+    }
+    if (!e.C || !aligned16(e.C)) return false;
   }
   return true;
 }
@@ -53,10 +58,12 @@ bool gemm_bf16_supported(const GemmDesc& d) {
 int gemm_bf16_launch(const GemmDesc& d, hipStream_t stream) {
   if (!gemm_bf16_supported(d)) return fail(MTF_ERR_UNSUPPORTED, "GEMM shape/alignment");
   GemmArgs a;
-  for (int s = 0; s < kMaxGroup; ++s) {
+  for (int s = 0; s < kMaxSlots; ++s) {
     a.A[s] = s < d.nseg ? d.A[s] : d.A[0];
     a.B[s] = s < d.nseg ? d.B[s] : d.B[0];
     a.K[s] = s < d.nseg ? (int)d.K[s] : 0;
+  }
+  for (int s = 0; s < kMaxGroup; ++s) {
     a.M[s] = (int)d.M;
     a.N[s] = (int)d.N;
     a.lda[s] = d.lda;
@@ -69,8 +76,12 @@ int gemm_bf16_launch(const GemmDesc& d, hipStream_t stream) {
   a.ngroup = 1 + d.nextra;
   for (int p = 0; p < d.nextra; ++p) {
     const GemmDesc::Extra& e = d.extra[p];
-    a.A[p + 1] = e.A; a.B[p + 1] = e.B; a.C[p + 1] = e.C;
-    a.M[p + 1] = (int)e.M; a.N[p + 1] = (int)e.N; a.K[p + 1] = (int)e.K;
+    for (int s = 0; s < d.nseg; ++s) {
+      const int slot = (p + 1) * d.nseg + s;
+      a.A[slot] = e.A[s]; a.B[slot] = e.B[s]; a.K[slot] = (int)e.K[s];
+    }
+    a.C[p + 1] = e.C;
+    a.M[p + 1] = (int)e.M; a.N[p + 1] = (int)e.N;
     a.lda[p + 1] = e.lda; a.ldb[p + 1] = e.ldb; a.ldc[p + 1] = e.ldc;
   }
   a.aux = d.aux;
@@ -93,7 +104,11 @@ int gemm_bf16_launch(const GemmDesc& d, hipStream_t stream) {
   };
   double k_total = 0;
   for (int s = 0; s < d.nseg; ++s) k_total += (double)d.K[s];
-  for (int p = 0; p < d.nextra; ++p) k_total = std::max(k_total, (double)d.extra[p].K);
+  for (int p = 0; p < d.nextra; ++p) {
+    double k_p = 0;
+    for (int s = 0; s < d.nseg; ++s) k_p += (double)d.extra[p].K[s];
+    k_total = std::max(k_total, k_p);
+  }
   const double block_us = 7.8 * k_total / 1024.0;
   const int64_t large_tiles = count(256, 256), medium_tiles = count(256, 128), small_tiles = count(128, 128);
   const double cost_large = (double)ceil_div(large_tiles, 256) * (4.0 * block_us + 5.0);

@@ -70,12 +70,12 @@ struct TileCfg {
   static_assert(WK == 1 || TM % 2 == 0, "k-groups split the wave tile's rows between them at the end");
 };
 
-// Slot s of A/B/K is k-segment s of one problem (ngroup == 1) or, in a grouped launch, the
-// operands of problem s (then every problem has one segment and its own M, N, C and leading dims).
+// Slot p * nseg + s of A/B/K is k-segment s of problem p (one problem unless the launch is
+// grouped; every problem of a group has nseg segments and its own M, N, C and leading dims).
 struct GemmArgs {
-  const bf16_t* A[kMaxGroup];
-  const bf16_t* B[kMaxGroup];
-  int K[kMaxGroup];
+  const bf16_t* A[kMaxSlots];
+  const bf16_t* B[kMaxSlots];
+  int K[kMaxSlots];
   int nseg, ngroup;
   int M[kMaxGroup], N[kMaxGroup];
   int64_t lda[kMaxGroup], ldb[kMaxGroup], ldc[kMaxGroup];
@@ -270,7 +270,7 @@ __global__ void __launch_bounds__(Cfg::kThreads, Cfg::kWavesPerSimd) gemm_bf16_k
   int total_tiles = 0;
 #pragma unroll
   for (int s = 0; s < kMaxSegments; ++s) {
-    const int slot = min(grp + s, kMaxGroup - 1);  // grp > 0 only with nseg == 1
+    const int slot = min(grp * g.nseg + s, kMaxSlots - 1);
     seg_a[s] = reinterpret_cast<const char*>(g.A[slot] + offA + a_tile0);
     seg_b[s] = reinterpret_cast<const char*>(g.B[slot] + offB + b_tile0);
     seg_k[s] = s < g.nseg ? g.K[slot] : 0;
@@ -636,8 +636,7 @@ int launch_instance(const GemmArgs& a, int batch, hipStream_t stream) {
     args.tiles_n[p] = (int)ceil_div(a.N[p], Cfg::BN);
     tiles = std::max<int64_t>(tiles, (int64_t)args.tiles_m[p] * args.tiles_n[p]);
     double ktot = 0;
-    if (a.ngroup > 1) ktot = a.K[p];
-    else for (int s = 0; s < a.nseg; ++s) ktot += a.K[s];
+    for (int s = 0; s < a.nseg; ++s) ktot += a.K[p * a.nseg + s];
     flops += 2.0 * a.M[p] * a.N[p] * ktot * batch;
     bytes += batch * (2.0 * ktot * (a.M[p] + a.N[p]) + (double)a.M[p] * a.N[p] * (OUT_BF16 ? 2 : 4));
   }

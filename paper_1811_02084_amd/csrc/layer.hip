@@ -12,7 +12,7 @@ namespace {
 
 inline size_t round256(size_t n) { return (n + 255) & ~size_t(255); }
 
-constexpr int kLayerPartials = 3;  // fp32 partial-sum buffers a layer step keeps in its workspace
+constexpr int kLayerPartials = 2;  // fp32 partial-sum buffers a layer step keeps in its workspace
 
 // C[M,N] = A op B with both operands given as plain row-major matrices:
 //   a_kc: A is [M,K] (k contiguous) else [K,M];   b_kc: B is [N,K] (k contiguous) else [K,N].
@@ -37,8 +37,11 @@ GemmDesc gemm(const void* A, bool a_kc, const void* B, bool b_kc, void* C, bool 
 // Appends problem `p` (one segment, same layouts / dtype as the group) to a grouped launch.
 void add_to_group(GemmDesc* group, const GemmDesc& p) {
   GemmDesc::Extra& e = group->extra[group->nextra++];
-  e.A = p.A[0]; e.B = p.B[0]; e.C = p.C;
-  e.M = p.M; e.N = p.N; e.K = p.K[0];
+  for (int s = 0; s < kMaxSegments; ++s) {
+    e.A[s] = p.A[s]; e.B[s] = p.B[s]; e.K[s] = p.K[s];
+  }
+  e.C = p.C;
+  e.M = p.M; e.N = p.N;
   e.lda = p.lda; e.ldb = p.ldb; e.ldc = p.ldc;
 }
 
@@ -70,6 +73,46 @@ int gemm_k_split(const void* A, bool a_kc, const void* B, bool b_kc, const Parti
   }
   if (int rc = gemm_bf16_launch(g, s)) return rc;
   return n;  // number of buffers actually written (positive)
+}
+
+// One contraction whose reduced dim runs through `npairs` operand pairs in turn (A_i [M,K] and
+// B_i [N,K], both k-contiguous, K elements each), cut into parts.n equal ranges of that
+// concatenated axis: range i -> buf[i], all ranges in one grouped launch.  A range that crosses
+// a pair boundary has one segment per pair it touches.  Returns the number of buffers written, or
+// 0 when the sizes do not allow the cut (nothing launched), or a negative error.
+int gemm_pairs_k_split(const bf16_t* const* A, const bf16_t* const* B, int npairs, int64_t K,
+                       const Partials& parts, int64_t M, int64_t N, hipStream_t s) {
+  const int n = parts.n;
+  const int64_t total = K * npairs;
+  if (n < 1 || n > kMaxGroup || total % (8 * n) || K % 8) return 0;
+  const int64_t kr = total / n;
+  GemmDesc range[kMaxGroup];
+  int nseg = 1;
+  for (int i = 0; i < n; ++i) {
+    GemmDesc& g = range[i];
+    g = gemm(nullptr, true, nullptr, true, parts.buf[i], false, M, N, 0);
+    g.lda = g.ldb = K;
+    int seg = 0;
+    for (int64_t k0 = i * kr; k0 < (i + 1) * kr;) {
+      const int pair = (int)(k0 / K);
+      const int64_t in_pair = k0 % K, len = std::min(K - in_pair, (i + 1) * kr - k0);
+      if (seg == kMaxSegments) return 0;
+      g.A[seg] = A[pair] + in_pair;
+      g.B[seg] = B[pair] + in_pair;
+      g.K[seg++] = len;
+      k0 += len;
+    }
+    nseg = std::max(nseg, seg);
+  }
+  if (n * nseg > kMaxSlots) return 0;
+  for (int i = 0; i < n; ++i) {  // unused segments: K = 0, pointers valid
+    for (int q = 0; q < nseg; ++q)
+      if (!range[i].A[q]) { range[i].A[q] = range[i].A[0]; range[i].B[q] = range[i].B[0]; }
+    range[i].nseg = nseg;
+    if (i > 0) add_to_group(&range[0], range[i]);
+  }
+  if (int rc = gemm_bf16_launch(range[0], s)) return rc;
+  return n;
 }
 
 int check_ptrs(std::initializer_list<const void*> ptrs, const char* what) {
@@ -197,13 +240,13 @@ int mha_bwd(const mtf_mha_dims* d, const void* x, const void* w_q, const void* w
   if (int rc = gemm_bf16_launch(dw, s)) return rc;
   // dx_partial = sum over {q,k,v} of einsum(d*[b,l,h,k], w_*[D,h,k] -> [b,l,D]): one contraction
   // whose reduced dims (h,k) are spread over three tensor pairs
-  GemmDesc g = gemm(w.dq, true, w_q, true, dx.buf[0], false, T, D, HK);
-  if (dx.n >= 3) {  // the three terms as three partial sums of one grouped launch
-    add_to_group(&g, gemm(w.dk, true, w_k, true, dx.buf[1], false, T, D, HK));
-    add_to_group(&g, gemm(w.dv, true, w_v, true, dx.buf[2], false, T, D, HK));
-    if (int rc = gemm_bf16_launch(g, s)) return rc;
-    return 3;
+  if (dx.n > 1) {  // the (h,k) axis of all three pairs, end to end, cut into dx.n equal ranges
+    const bf16_t* as[3] = {w.dq, w.dk, w.dv};
+    const bf16_t* bs[3] = {static_cast<const bf16_t*>(w_q), static_cast<const bf16_t*>(w_k),
+                           static_cast<const bf16_t*>(w_v)};
+    if (int n = gemm_pairs_k_split(as, bs, 3, HK, dx, T, D, s)) return n;
   }
+  GemmDesc g = gemm(w.dq, true, w_q, true, dx.buf[0], false, T, D, HK);
   g.nseg = 3;  // one output: the three (A, B) pairs are consecutive ranges of one reduction
   g.A[1] = w.dk; g.B[1] = static_cast<const bf16_t*>(w_k); g.K[1] = HK;
   g.A[2] = w.dv; g.B[2] = static_cast<const bf16_t*>(w_v); g.K[2] = HK;
@@ -402,9 +445,9 @@ int mtf_layer_bwd(const mtf_layer_dims* d, const void* x, const mtf_layer_weight
   if (int rc = residual_add(carve(p, 2, count), n, dz, du, count, s)) return rc;
   // attention sublayer: dx = du + R(dx_mha_partial)
   n = mha_bwd(&m, x, w->w_q, w->w_k, w->w_v, w->w_o, sv->q, sv->k, sv->v, sv->ctx, sv->lse, du, scale, causal,
-              g->dw_q, g->dw_k, g->dw_v, g->dw_o, carve(p, 3, count), mha_bwd_scratch(&m, rest), s);
+              g->dw_q, g->dw_k, g->dw_v, g->dw_o, carve(p, 2, count), mha_bwd_scratch(&m, rest), s);
   if (n < 0) return n;
-  return residual_add(carve(p, 3, count), n, du, dx, count, s);
+  return residual_add(carve(p, 2, count), n, du, dx, count, s);
 }
 
 }  // extern "C"
