@@ -293,6 +293,15 @@ def main():
                     mfma_busy=profile_field("layer_config5_counters.txt", args.workload, dom["kernel"], "mfma_busy"),
                     kernel=dom["kernel"], launches_per_step=dom["launches"] // args.steps,
                     avg_launch_us=round(avg_ms * 1e3, 2), mfma_only_measured_tflops=mfma_only)
+    # the kernel above is the one with the most time per step (all its launches together); the
+    # single longest launch of the step is reported beside it when it is another kernel
+    longest = max(kinds, key=lambda r: r["total_ms"] / r["launches"])
+    if longest is not dom and longest["flops"] > 0:
+        l_ms = longest["total_ms"] / longest["launches"]
+        l_tf = longest["flops"] / longest["launches"] / (l_ms * 1e-3) / 1e12
+        roofline["longest_launch"] = dict(kernel=longest["kernel"], launches_per_step=longest["launches"] // args.steps,
+                                          avg_launch_us=round(l_ms * 1e3, 2), achieved=round(l_tf, 1),
+                                          frac=round(l_tf / PEAK_BF16_TFLOPS, 4))
     all_ms = sum(r["total_ms"] for r in kinds)
     gemm = [r for r in kinds if r["kernel"].startswith("gemm_bf16_kernel")]
     breakdown = {r["kernel"]: dict(us_per_step=round(r["total_ms"] * 1e3 / args.steps, 1),

@@ -86,6 +86,7 @@ struct GemmArgs {
   float alpha;
   int accumulate;
   int tiles_m[kMaxGroup], tiles_n[kMaxGroup];
+  int xcds_per_problem;  // grouped launch: > 0 when every XCD works on one problem only, else 0
   int batch1;
   int64_t sA0, sA1, sB0, sB1, sC0, sC1;
 };
@@ -220,11 +221,24 @@ __global__ void __launch_bounds__(Cfg::kThreads, Cfg::kWavesPerSimd) gemm_bf16_k
   __shared__ __attribute__((aligned(1024))) char ring[NS * Cfg::kStage];
 
   // ---- which tile: XCD-aware remap, then patches of kGroupM tile rows
-  const int grp = g.ngroup > 1 ? blockIdx.y : 0;  // grouped launch: blockIdx.y picks the problem
+  // Workgroups go to the 8 XCDs round-robin in dispatch order (gridDim.x is a multiple of 8), and
+  // each XCD has an L2 of its own.  One problem: XCD x takes a contiguous run of the tile order
+  // below.  A group of equally sized problems, 1, 2 or 4 XCDs per problem: an XCD takes tiles of
+  // one problem only, so that it fetches that problem's operands and nobody else's (with every
+  // problem spread over all XCDs, each XCD fetched the narrow operand of every problem).
+  // Otherwise blockIdx.y picks the problem and each problem is spread over all XCDs.
+  int grp, t;
+  if (g.xcds_per_problem > 0) {
+    const int flat = blockIdx.y * gridDim.x + blockIdx.x, xcd = flat & 7, slot = flat >> 3;
+    const int per_xcd = (gridDim.x * g.ngroup) >> 3;
+    grp = xcd / g.xcds_per_problem;
+    t = (xcd % g.xcds_per_problem) * per_xcd + slot;
+  } else {
+    grp = g.ngroup > 1 ? blockIdx.y : 0;
+    t = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
+  }
   const int M = g.M[grp], N = g.N[grp], tiles_m = g.tiles_m[grp], tiles_n = g.tiles_n[grp];
   const int64_t lda = g.lda[grp], ldb = g.ldb[grp], ldc = g.ldc[grp];
-  const int per_xcd = gridDim.x >> 3;
-  const int t = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
   if (t >= tiles_m * tiles_n) return;
   const int per_group = Cfg::kGroupM * tiles_n;
   const int first_m = (t / per_group) * Cfg::kGroupM;
@@ -641,6 +655,10 @@ int launch_instance(const GemmArgs& a, int batch, hipStream_t stream) {
     bytes += batch * (2.0 * ktot * (a.M[p] + a.N[p]) + (double)a.M[p] * a.N[p] * (OUT_BF16 ? 2 : 4));
   }
   if (tiles > (1 << 28)) return fail(MTF_ERR_UNSUPPORTED, "too many tiles");
+  bool same_count = true;
+  for (int p = 1; p < a.ngroup; ++p)
+    same_count = same_count && args.tiles_m[p] * args.tiles_n[p] == args.tiles_m[0] * args.tiles_n[0];
+  args.xcds_per_problem = (a.ngroup > 1 && 8 % a.ngroup == 0 && same_count) ? 8 / a.ngroup : 0;
   dim3 grid((unsigned)(ceil_div(tiles, 8) * 8), (unsigned)(a.ngroup > 1 ? a.ngroup : batch), 1);
   LaunchTimer timer(name, flops, bytes, stream);
   gemm_bf16_kernel<Cfg, A_K, B_K, EPI, OUT_BF16><<<grid, Cfg::kThreads, 0, stream>>>(args);
