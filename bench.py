@@ -139,8 +139,8 @@ def main():
         # config 7: the worked example's 3-D layout (batch -> rows, d_ff -> cols, d_model -> planes) on
         # a VIRTUAL 2x2x2 mesh held on this one GPU, forward and backward: on every processor each of
         # the six einsums leaves a partial sum (section "Data-Parallel, Model-Parallel Layouts",
-        # last layout), which the reduce kernel sums over the mesh dim the einsum's plan names; the
-        # ReLU and its mask are component-wise passes between them
+        # last layout), which the reduce kernel sums over the mesh dim the einsum's plan names (once
+        # per group of processors that differ only along that dim), applying the ReLU resp. its mask
         cfg = mtf_inputs.config7()
         mesh, layout = cfg["mesh"], cfg["layout"]
         B, L, D = cfg["x"].shape
@@ -162,17 +162,25 @@ def main():
         group = lambda c, ax: [c2 for c2 in coords if all(c2[i] == c[i] for i in range(3) if i not in ax)]
         f32, bf16 = torch.float32, torch.bfloat16
 
-        def reduced(parts, ax, dt):
-            return {c: mtf.reduce_partials([parts[c2] for c2 in group(c, ax)], out_dtype=dt) for c in coords}
+        def reduced(parts, ax, dt, epi=mtf.EPI_NONE, aux=None):
+            # every processor of a group ends with the same sum: taken once per group and shared
+            done = {}
+            for c in coords:
+                members = tuple(group(c, ax))
+                if members not in done:
+                    done[members] = mtf.reduce_partials([parts[c2] for c2 in members], out_dtype=dt, epi=epi,
+                                                        aux=None if aux is None else aux[c])
+            return {c: done[tuple(group(c, ax))] for c in coords}
 
         def step():
+            # the ReLU and the mask of its gradient ride on the reduce that completes their operand
             es = mtf.einsum_local
-            h = reduced({c: es(xs[c], X, wi[c], WI, HID, out_dtype=f32) for c in coords}, plan["h"], bf16)
-            a = {c: es(h[c], HID, None, None, HID, epi=mtf.EPI_RELU) for c in coords}
+            a = reduced({c: es(xs[c], X, wi[c], WI, HID, out_dtype=f32) for c in coords}, plan["h"], bf16,
+                        mtf.EPI_RELU)
             y = reduced({c: es(a[c], HID, wo[c], WO, X, out_dtype=f32) for c in coords}, plan["y"], f32)
             dwo = reduced({c: es(a[c], HID, dys[c], X, WO, out_dtype=f32) for c in coords}, plan["dwo"], f32)
-            da = reduced({c: es(dys[c], X, wo[c], WO, HID, out_dtype=f32) for c in coords}, plan["da"], bf16)
-            dh = {c: es(da[c], HID, None, None, HID, epi=mtf.EPI_MASK_GT0, aux=a[c]) for c in coords}
+            dh = reduced({c: es(dys[c], X, wo[c], WO, HID, out_dtype=f32) for c in coords}, plan["da"], bf16,
+                         mtf.EPI_MASK_GT0, a)
             dwi = reduced({c: es(xs[c], X, dh[c], HID, WI, out_dtype=f32) for c in coords}, plan["dwi"], f32)
             dx = reduced({c: es(dh[c], HID, wi[c], WI, X, out_dtype=f32) for c in coords}, plan["dx"], f32)
             return y, dwo, dwi, dx

@@ -26,7 +26,8 @@
  *     machine without one.
  *
  * Contents: slices and lowering plans (host); slice gather, the local einsum with its fused
- * epilogues, partial-sum reduce (the Allreduce stand-in on a virtual mesh), the data-parallel
+ * epilogues, partial-sum reduce (the Allreduce stand-in on a virtual mesh; also with a
+ * component-wise epilogue), the data-parallel
  * training step; component-wise
  * addition with implicit broadcasting, local reductions; reshape on a virtual mesh (renaming,
  * and changing rank or sizes); layer normalisation over d_model; the vocabulary-split operations;
@@ -188,6 +189,17 @@ int mtf_einsum_local_path(const void* a, const mtf_shape* a_local, const void* b
 int mtf_reduce_partials(const void* const* partials, int32_t n, const void* residual,
                         mtf_dtype residual_dt, void* out, mtf_dtype out_dt, int64_t count,
                         void* stream);
+/* The same with a component-wise operation on the complete sum (section "Operation
+ * Implementation", component-wise paragraph: no communication, so it can ride on the pass that
+ * ends the Allreduce): MTF_EPI_RELU: out = max(sum, 0); MTF_EPI_MASK_GT0: out = aux > 0 ?
+ * sum : 0 with aux a DEVICE bf16 buffer of `count` elements (the saved activation: the ReLU
+ * gradient).  In the layouts that split d_model the pre-activation is itself a partial sum, so
+ * the ReLU can only follow the reduce; this is that pair in one pass.  Bit-identical to
+ * mtf_reduce_partials followed by the component-wise mtf_einsum_local.
+ * Errors: as mtf_reduce_partials; UNSUPPORTED for any other epilogue; NULL / ALIGN for aux. */
+int mtf_reduce_partials_epi(const void* const* partials, int32_t n, const void* residual,
+                            mtf_dtype residual_dt, void* out, mtf_dtype out_dt, int64_t count,
+                            mtf_epilogue epi, const void* aux, void* stream);
 
 /* ---------------------------------------------------------------- device: the data-parallel training step
  * Section "Inspiration: Single-Program-Multiple-Data (SPMD) Batch-Splitting", Algorithm 1, steps

@@ -312,7 +312,8 @@ def einsum_local_path(a_dims, b_dims, out_dims, in_dtype=torch.bfloat16, out_dty
     return rc
 
 
-def reduce_partials(partials, residual=None, out_dtype=torch.float32, out=None):
+def reduce_partials(partials, residual=None, out_dtype=torch.float32, out=None, epi=EPI_NONE, aux=None):
+    """epi / aux: component-wise operation on the complete sum (mtf_reduce_partials_epi)."""
     n = len(partials)
     count = partials[0].numel()
     arr = (C.c_void_p * n)(*[p.data_ptr() for p in partials])
@@ -321,8 +322,10 @@ def reduce_partials(partials, residual=None, out_dtype=torch.float32, out=None):
             raise ValueError("partials must be contiguous fp32 tensors of one size")
     if out is None:
         out = torch.empty(partials[0].shape, dtype=out_dtype, device=partials[0].device)
-    _check(lib.mtf_reduce_partials(arr, n, _ptr(residual), _dt(residual) if residual is not None else F32,
-                                   _ptr(out), _dt(out), C.c_int64(count), _stream()))
+    if aux is not None and (aux.dtype != torch.bfloat16 or aux.numel() != count or not aux.is_contiguous()):
+        raise ValueError("aux must be a contiguous bf16 tensor of the partials' size")
+    _check(lib.mtf_reduce_partials_epi(arr, n, _ptr(residual), _dt(residual) if residual is not None else F32,
+                                       _ptr(out), _dt(out), C.c_int64(count), int(epi), _ptr(aux), _stream()))
     return out
 
 

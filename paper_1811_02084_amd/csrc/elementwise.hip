@@ -103,7 +103,8 @@ struct PartialPtrs {
 template <bool RES_BF16, bool OUT_BF16, int NFIX>
 __global__ void __launch_bounds__(256) reduce_partials_kernel(PartialPtrs parts, int n,
                                                              const void* __restrict__ residual,
-                                                             void* __restrict__ out, int64_t count) {
+                                                             void* __restrict__ out, int64_t count, int epi,
+                                                             const bf16_t* __restrict__ aux) {
   const int64_t vecs = count / 8;
   for (int64_t v = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; v < vecs;
        v += (int64_t)gridDim.x * blockDim.x) {
@@ -116,6 +117,8 @@ __global__ void __launch_bounds__(256) reduce_partials_kernel(PartialPtrs parts,
         x[i][1] = reinterpret_cast<const float4*>(parts.p[i])[2 * v + 1];
       }
     }
+    uint4 m = make_uint4(0u, 0u, 0u, 0u);  // the mask operand travels with the partials
+    if (epi == MTF_EPI_MASK_GT0) m = reinterpret_cast<const uint4*>(aux)[v];
     if (residual) {
       if (RES_BF16) {
         const uint4 r = reinterpret_cast<const uint4*>(residual)[v];
@@ -144,6 +147,18 @@ __global__ void __launch_bounds__(256) reduce_partials_kernel(PartialPtrs parts,
       for (int i = 0; i < n; ++i)
         add(reinterpret_cast<const float4*>(parts.p[i])[2 * v], reinterpret_cast<const float4*>(parts.p[i])[2 * v + 1]);
     }
+    // component-wise epilogue on the complete sum (one branch, uniform over the launch)
+    if (epi == MTF_EPI_RELU) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[e] = fmaxf(acc[e], 0.f);
+    } else if (epi == MTF_EPI_MASK_GT0) {
+      const uint32_t w[4] = {m.x, m.y, m.z, m.w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        acc[2 * e] = __uint_as_float(w[e] << 16) > 0.f ? acc[2 * e] : 0.f;
+        acc[2 * e + 1] = __uint_as_float(w[e] & 0xffff0000u) > 0.f ? acc[2 * e + 1] : 0.f;
+      }
+    }
     if (OUT_BF16) {
       reinterpret_cast<uint4*>(out)[v] = make_uint4(pack_bf16x2(acc[0], acc[1]), pack_bf16x2(acc[2], acc[3]),
                                                    pack_bf16x2(acc[4], acc[5]), pack_bf16x2(acc[6], acc[7]));
@@ -160,6 +175,8 @@ __global__ void __launch_bounds__(256) reduce_partials_kernel(PartialPtrs parts,
       acc = RES_BF16 ? bf16_to_f32(static_cast<const bf16_t*>(residual)[t])
                      : static_cast<const float*>(residual)[t];
     for (int i = 0; i < n; ++i) acc += parts.p[i][t];
+    if (epi == MTF_EPI_RELU) acc = fmaxf(acc, 0.f);
+    if (epi == MTF_EPI_MASK_GT0) acc = bf16_to_f32(aux[t]) > 0.f ? acc : 0.f;
     if (OUT_BF16)
       static_cast<bf16_t*>(out)[t] = f32_to_bf16(acc);
     else
@@ -250,7 +267,18 @@ int mtf_slice_copy(void* full, void* slice, const mtf_shape* t, const mtf_place*
 int mtf_reduce_partials(const void* const* partials, int32_t n, const void* residual,
                         mtf_dtype residual_dt, void* out, mtf_dtype out_dt, int64_t count,
                         void* stream) {
+  return mtf_reduce_partials_epi(partials, n, residual, residual_dt, out, out_dt, count, MTF_EPI_NONE, nullptr,
+                                 stream);
+}
+
+int mtf_reduce_partials_epi(const void* const* partials, int32_t n, const void* residual,
+                            mtf_dtype residual_dt, void* out, mtf_dtype out_dt, int64_t count,
+                            mtf_epilogue epi, const void* aux, void* stream) {
   if (!partials) return fail(MTF_ERR_NULL, "partials");
+  if (epi != MTF_EPI_NONE && epi != MTF_EPI_RELU && epi != MTF_EPI_MASK_GT0)
+    return fail(MTF_ERR_UNSUPPORTED, "epilogue %d of a partial-sum reduce", (int)epi);
+  if (epi == MTF_EPI_MASK_GT0 && count > 0 && !aux) return fail(MTF_ERR_NULL, "aux");
+  if (epi == MTF_EPI_MASK_GT0 && !aligned16(aux)) return fail(MTF_ERR_ALIGN, "aux");
   if (n < 1 || n > 64) return fail(MTF_ERR_UNSUPPORTED, "%d partials (1..64)", n);
   if (count < 0) return fail(MTF_ERR_SIZE_MISMATCH, "count %lld", (long long)count);
   if (count == 0) return MTF_OK;  // nothing to sum: buffers may legitimately be empty (NULL)
@@ -266,16 +294,19 @@ int mtf_reduce_partials(const void* const* partials, int32_t n, const void* resi
   int blocks = (int)std::min<int64_t>(ceil_div(ceil_div(count, 8), 256), 256 * 8);
   bool rb = residual && residual_dt == MTF_BF16, ob = out_dt == MTF_BF16;
   LaunchTimer timer("reduce_partials_kernel", 0,
-                    (double)count * (4.0 * n + (residual ? (rb ? 2 : 4) : 0) + (ob ? 2 : 4)), s);
+                    (double)count * (4.0 * n + (residual ? (rb ? 2 : 4) : 0) + (ob ? 2 : 4) +
+                                     (epi == MTF_EPI_MASK_GT0 ? 2 : 0)), s);
+  const int e = (int)epi;
+  const bf16_t* ax = static_cast<const bf16_t*>(aux);
   // one vector per thread (count / 8 threads) up to 8 workgroups per CU, grid-stride beyond
   auto launch = [&](auto res_bf16, auto out_bf16) {
     constexpr bool RB = decltype(res_bf16)::value, OB = decltype(out_bf16)::value;
     switch (n) {
-      case 1: reduce_partials_kernel<RB, OB, 1><<<blocks, 256, 0, s>>>(pp, n, residual, out, count); break;
-      case 2: reduce_partials_kernel<RB, OB, 2><<<blocks, 256, 0, s>>>(pp, n, residual, out, count); break;
-      case 3: reduce_partials_kernel<RB, OB, 3><<<blocks, 256, 0, s>>>(pp, n, residual, out, count); break;
-      case 4: reduce_partials_kernel<RB, OB, 4><<<blocks, 256, 0, s>>>(pp, n, residual, out, count); break;
-      default: reduce_partials_kernel<RB, OB, 0><<<blocks, 256, 0, s>>>(pp, n, residual, out, count); break;
+      case 1: reduce_partials_kernel<RB, OB, 1><<<blocks, 256, 0, s>>>(pp, n, residual, out, count, e, ax); break;
+      case 2: reduce_partials_kernel<RB, OB, 2><<<blocks, 256, 0, s>>>(pp, n, residual, out, count, e, ax); break;
+      case 3: reduce_partials_kernel<RB, OB, 3><<<blocks, 256, 0, s>>>(pp, n, residual, out, count, e, ax); break;
+      case 4: reduce_partials_kernel<RB, OB, 4><<<blocks, 256, 0, s>>>(pp, n, residual, out, count, e, ax); break;
+      default: reduce_partials_kernel<RB, OB, 0><<<blocks, 256, 0, s>>>(pp, n, residual, out, count, e, ax); break;
     }
   };
   if (rb && ob)

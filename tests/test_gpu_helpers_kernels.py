@@ -75,6 +75,46 @@ def test_reduce_partials(n, count):
     assert np.array_equal(got.cpu().numpy(), sum(ints))
 
 
+@pytest.mark.parametrize("count", [5, 1027, 1 << 18])
+@pytest.mark.parametrize("n", [2, 4, 7])
+def test_reduce_partials_with_a_componentwise_epilogue(n, count):
+    """ReLU, and the ReLU gradient's mask, applied to the complete sum by the reduce itself
+    (mtf_reduce_partials_epi): against the definition in fp64, bit-exact on integer-valued partials,
+    and bit-identical to the reduce followed by the component-wise pass."""
+    print(f"reduce_partials_epi n={n} count={count}", flush=True)
+    rng = np.random.default_rng(n * 7919 + count)
+    parts = [rng.standard_normal(count).astype(np.float32) for _ in range(n)]
+    dparts = [torch.from_numpy(p).cuda() for p in parts]
+    total = sum(p.astype(np.float64) for p in parts)
+    aux = rng.standard_normal(count).astype(np.float32)
+    aux[::5] = 0.0                                   # exactly zero: gradient 0 there
+    aux[1::11] = -0.0
+    daux = torch.from_numpy(aux).to(torch.bfloat16).cuda()
+    visible = daux.float().cpu().numpy() > 0.0
+    dims = [("i", count)]
+    for dt, tol in ((torch.float32, F32_TOL), (torch.bfloat16, 2.0 ** -8)):
+        got = mtf.reduce_partials(dparts, out_dtype=dt, epi=mtf.EPI_RELU)
+        assert m2(f64(got), np.maximum(total, 0.0)) <= tol
+        assert not bool((got.float() < 0).any())
+        got = mtf.reduce_partials(dparts, out_dtype=dt, epi=mtf.EPI_MASK_GT0, aux=daux)
+        assert m2(f64(got), np.where(visible, total, 0.0)) <= tol
+        assert not bool(got.float()[torch.from_numpy(~visible).cuda()].any())
+    if count % 8 == 0:                               # the component-wise path of the einsum call takes whole vectors
+        plain = mtf.reduce_partials(dparts, out_dtype=torch.bfloat16)
+        two_pass = mtf.einsum_local(plain, ("i",), None, None, ("i",), epi=mtf.EPI_RELU)
+        assert torch.equal(mtf.reduce_partials(dparts, out_dtype=torch.bfloat16, epi=mtf.EPI_RELU), two_pass)
+        two_pass = mtf.einsum_local(plain, ("i",), None, None, ("i",), epi=mtf.EPI_MASK_GT0, aux=daux)
+        assert torch.equal(mtf.reduce_partials(dparts, out_dtype=torch.bfloat16, epi=mtf.EPI_MASK_GT0, aux=daux),
+                           two_pass)
+    ints = [rng.integers(-8, 9, count).astype(np.float32) for _ in range(n)]
+    got = mtf.reduce_partials([torch.from_numpy(p).cuda() for p in ints], epi=mtf.EPI_RELU)
+    assert np.array_equal(got.cpu().numpy(), np.maximum(sum(ints), 0))
+    res = torch.from_numpy(rng.integers(-8, 9, count).astype(np.float32)).to(torch.bfloat16)
+    got = mtf.reduce_partials([torch.from_numpy(p).cuda() for p in ints], residual=res.cuda(), out_dtype=torch.float32,
+                              epi=mtf.EPI_MASK_GT0, aux=daux)
+    assert np.array_equal(got.cpu().numpy(), np.where(visible, sum(ints) + res.float().numpy(), 0))
+
+
 def test_cast_rounds_to_nearest_even_bit_exact():
     rng = np.random.default_rng(5)
     x = (rng.standard_normal(1 << 18) * np.exp(rng.uniform(-30, 30, 1 << 18))).astype(np.float32)

@@ -128,28 +128,34 @@ def _mesh3d_tools(g, mesh, layout, coords):
     axes = lambda p, q, out: mtf.einsum_plan(shp(p), shp(q), shp(out), mesh, layout)["reduce_axes"]
     group = lambda c, ax: [c2 for c2 in coords if all(c2[i] == c[i] for i in range(len(mesh)) if i not in ax)]
     sl = lambda name, dims: {c: mtf.slice_copy(g[name], dims, mesh, layout, c) for c in coords}
-    reduced = lambda parts, ax, dtype: {c: mtf.reduce_partials([parts[c2] for c2 in group(c, ax)], out_dtype=dtype)
-                                        for c in coords}
+    # epi / aux: a component-wise operation riding on the reduce (aux per processor)
+    reduced = lambda parts, ax, dtype, epi=mtf.EPI_NONE, aux=None: {
+        c: mtf.reduce_partials([parts[c2] for c2 in group(c, ax)], out_dtype=dtype, epi=epi,
+                               aux=None if aux is None else aux[c]) for c in coords}
     return axes, sl, reduced
 
 
-def _mesh3d_forward(g, mesh, layout, coords):
+def _mesh3d_forward(g, mesh, layout, coords, fused=False):
     """Every einsum leaves partial sums (section "Data-Parallel, Model-Parallel Layouts", last
     layout), each summed over the mesh dim its plan names; the ReLU is a component-wise operation
-    applied once the hidden layer's sum is complete.  Returns per-processor a and y."""
+    applied once the hidden layer's sum is complete - as a pass of its own, or (fused) by the pass
+    that completes the sum.  Returns per-processor a and y."""
     axes, sl, reduced = _mesh3d_tools(g, mesh, layout, coords)
     xs, wi, wo = sl("x", X), sl("w_in", WI), sl("w_out", WO)
     ax_h, ax_y = axes(X, WI, HID), axes(HID, WO, X)
     assert ax_h == [2] and ax_y == [1]                          # over planes, then over cols
-    h = reduced({c: mtf.einsum_local(xs[c], X, wi[c], WI, HID, out_dtype=torch.float32) for c in coords}, ax_h,
-                torch.bfloat16)
-    a = {c: mtf.einsum_local(h[c], HID, None, None, HID, epi=mtf.EPI_RELU) for c in coords}
+    h_parts = {c: mtf.einsum_local(xs[c], X, wi[c], WI, HID, out_dtype=torch.float32) for c in coords}
+    if fused:
+        a = reduced(h_parts, ax_h, torch.bfloat16, mtf.EPI_RELU)
+    else:
+        h = reduced(h_parts, ax_h, torch.bfloat16)
+        a = {c: mtf.einsum_local(h[c], HID, None, None, HID, epi=mtf.EPI_RELU) for c in coords}
     y = reduced({c: mtf.einsum_local(a[c], HID, wo[c], WO, X, out_dtype=torch.float32) for c in coords}, ax_y,
                 torch.float32)
     return dict(a=a, y=y)
 
 
-def _mesh3d_backward(g, mesh, layout, coords, a):
+def _mesh3d_backward(g, mesh, layout, coords, a, fused=False):
     """Backward from given per-processor activations `a`: four more einsums, each a partial sum."""
     axes, sl, reduced = _mesh3d_tools(g, mesh, layout, coords)
     xs, wi, wo, dys = sl("x", X), sl("w_in", WI), sl("w_out", WO), sl("dy", X)
@@ -158,9 +164,13 @@ def _mesh3d_backward(g, mesh, layout, coords, a):
     out = {}
     out["dw_out"] = reduced({c: mtf.einsum_local(a[c], HID, dys[c], X, WO, out_dtype=torch.float32) for c in coords},
                             ax_dwo, torch.float32)
-    da = reduced({c: mtf.einsum_local(dys[c], X, wo[c], WO, HID, out_dtype=torch.float32) for c in coords}, ax_da,
-                 torch.bfloat16)
-    dh = {c: mtf.einsum_local(da[c], HID, None, None, HID, epi=mtf.EPI_MASK_GT0, aux=a[c]) for c in coords}
+    da_parts = {c: mtf.einsum_local(dys[c], X, wo[c], WO, HID, out_dtype=torch.float32) for c in coords}
+    if fused:
+        dh = reduced(da_parts, ax_da, torch.bfloat16, mtf.EPI_MASK_GT0, a)
+    else:
+        da = reduced(da_parts, ax_da, torch.bfloat16)
+        dh = {c: mtf.einsum_local(da[c], HID, None, None, HID, epi=mtf.EPI_MASK_GT0, aux=a[c]) for c in coords}
+    out["dh"] = dh
     out["dw_in"] = reduced({c: mtf.einsum_local(xs[c], X, dh[c], HID, WI, out_dtype=torch.float32) for c in coords},
                            ax_dwi, torch.float32)
     out["dx"] = reduced({c: mtf.einsum_local(dh[c], HID, wi[c], WI, X, out_dtype=torch.float32) for c in coords},
@@ -207,6 +217,14 @@ def test_three_dimensional_layout_at_shard_size_bf16():
             err = m2(f64(got[k][c]), want.data)
             assert err <= BF16_TOL, (k, c, err)
     print("3-D layout: all slices within tolerance", flush=True)
+    # the ReLU and its gradient mask applied by the reduce that completes the sum: the same bits
+    print("3-D layout: component-wise operations fused into the reduces", flush=True)
+    fwd2 = _mesh3d_forward(g, mesh, layout, coords, fused=True)
+    got2 = _mesh3d_backward(g, mesh, layout, coords, a_ref, fused=True)
+    for c in coords:
+        assert torch.equal(fwd2["a"][c], fwd["a"][c]) and torch.equal(fwd2["y"][c], fwd["y"][c]), c
+        for k in ("dh", "dw_in", "dw_out", "dx"):
+            assert torch.equal(got2[k][c], got[k][c]), (k, c)
 
 
 def to_dev_bf16(arr):

@@ -142,6 +142,10 @@ def test_argument_validation_needs_no_gpu():
     arr = (C.c_void_p * 1)(None)
     assert lib.mtf_reduce_partials(arr, 1, None, 0, None, 0, C.c_int64(0), None) == 0        # empty: nothing to do
     assert b"MTF_ERR" in lib.mtf_last_error()
+    one = (C.c_void_p * 1)(4096)
+    assert lib.mtf_reduce_partials_epi(one, 1, None, 0, p, 0, C.c_int64(8), 3, None, None) == -10   # no such epilogue here
+    assert lib.mtf_reduce_partials_epi(one, 1, None, 0, p, 0, C.c_int64(8), 2, None, None) == -1    # mask without aux
+    assert lib.mtf_reduce_partials_epi(one, 1, None, 0, p, 0, C.c_int64(8), 2, C.c_void_p(4098), None) == -14
     # the worked example with its bias, broadcasting addition, local reduction
     assert lib.mtf_ffn_bias_fwd(C.byref(d), p, p, None, p, p, p, None) == -1                     # bias NULL
     assert lib.mtf_ffn_bias_bwd(C.byref(d), p, p, p, p, p, p, p, p, p, None, C.c_size_t(0), None) == -11
