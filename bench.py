@@ -168,21 +168,25 @@ def main():
             for c in coords:
                 members = tuple(group(c, ax))
                 if members not in done:
-                    done[members] = mtf.reduce_partials([parts[c2] for c2 in members], out_dtype=dt, epi=epi,
+                    bufs = [t for c2 in members for t in (parts[c2] if isinstance(parts[c2], list) else [parts[c2]])]
+                    done[members] = mtf.reduce_partials(bufs, out_dtype=dt, epi=epi,
                                                         aux=None if aux is None else aux[c])
             return {c: done[tuple(group(c, ax))] for c in coords}
 
         def step():
             # the ReLU and the mask of its gradient ride on the reduce that completes their operand
+            # the four einsums with a 512-wide output side run as 2 ranges of their contracted dim
+            # (their partial sums go into the same reduce): 128 tiles for 256 CUs otherwise
             es = mtf.einsum_local
+            kr = lambda p, pd, q, qd, od: mtf.einsum_local_kranges(p, pd, q, qd, od, 2)
             a = reduced({c: es(xs[c], X, wi[c], WI, HID, out_dtype=f32) for c in coords}, plan["h"], bf16,
                         mtf.EPI_RELU)
-            y = reduced({c: es(a[c], HID, wo[c], WO, X, out_dtype=f32) for c in coords}, plan["y"], f32)
-            dwo = reduced({c: es(a[c], HID, dys[c], X, WO, out_dtype=f32) for c in coords}, plan["dwo"], f32)
+            y = reduced({c: kr(a[c], HID, wo[c], WO, X) for c in coords}, plan["y"], f32)
+            dwo = reduced({c: kr(a[c], HID, dys[c], X, WO) for c in coords}, plan["dwo"], f32)
             dh = reduced({c: es(dys[c], X, wo[c], WO, HID, out_dtype=f32) for c in coords}, plan["da"], bf16,
                          mtf.EPI_MASK_GT0, a)
-            dwi = reduced({c: es(xs[c], X, dh[c], HID, WI, out_dtype=f32) for c in coords}, plan["dwi"], f32)
-            dx = reduced({c: es(dh[c], HID, wi[c], WI, X, out_dtype=f32) for c in coords}, plan["dx"], f32)
+            dwi = reduced({c: kr(xs[c], X, dh[c], HID, WI) for c in coords}, plan["dwi"], f32)
+            dx = reduced({c: kr(dh[c], HID, wi[c], WI, X) for c in coords}, plan["dx"], f32)
             return y, dwo, dwi, dx
     elif args.workload == "attention_lm":
         # the attention core at the head width of the paper's language models (d_k = d_v = 256):

@@ -164,6 +164,20 @@ int mtf_einsum_local(const void* a, const mtf_shape* a_local, const void* b,
                      mtf_dtype in_dt, mtf_dtype out_dt, mtf_epilogue epi, const void* aux,
                      float alpha, int accumulate, void* stream);
 
+/* The same einsum with its contracted dim cut into n (1..4) equal ranges, as one launch:
+ * outs[i] (fp32, each of the output's local shape) receives the sum over range i, and their sum
+ * is the einsum.  For einsums whose output is too narrow to give every CU a tile and whose
+ * result is a partial sum on its way into mtf_reduce_partials anyway (a contracted, split dim;
+ * einsum paragraph of "Operation Implementation"): the reduce then simply takes n times as many
+ * buffers - on one GPU the same thing the layout does across processors when it splits a
+ * reduced-out dim.  bf16 operands that fold to one matrix product without batch dims only
+ * (mtf_einsum_local_path says MTF_PATH_MFMA for them) and a contracted size divisible by 8 n;
+ * anything else is MTF_ERR_UNSUPPORTED and nothing is launched.  outs: HOST array of n DEVICE
+ * pointers.  Errors: as mtf_einsum_local. */
+int mtf_einsum_local_kranges(const void* a, const mtf_shape* a_local, const void* b,
+                             const mtf_shape* b_local, void* const* outs, int32_t n,
+                             const mtf_shape* out_local, void* stream);
+
 /* Which kernel mtf_einsum_local would run for exactly these arguments: MTF_PATH_MFMA (the bf16
  * matrix-core kernel) or MTF_PATH_GENERIC (one thread per output element, fp32 FMA: the same
  * result up to summation order, one to two orders of magnitude slower at layer sizes), or the

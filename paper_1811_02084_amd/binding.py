@@ -291,6 +291,21 @@ def einsum_local(a, a_dims, b, b_dims, out_dims, out_dtype=None, epi=EPI_NONE, a
     return out
 
 
+def einsum_local_kranges(a, a_dims, b, b_dims, out_dims, n, outs=None):
+    """The einsum with its contracted dim cut into n ranges: a list of n fp32 partial sums."""
+    k = _Keep()
+    sa, sb = k.shape(_named(a, a_dims)), k.shape(_named(b, b_dims))
+    sizes = dict(_named(a, a_dims))
+    sizes.update(_named(b, b_dims))
+    out_shape = [(d, sizes.get(d, 1)) for d in out_dims]
+    if outs is None:
+        outs = [torch.empty([s for _, s in out_shape], dtype=torch.float32, device=a.device) for _ in range(n)]
+    so = k.shape(out_shape)
+    arr = (C.c_void_p * n)(*[o.data_ptr() for o in outs])
+    _check(lib.mtf_einsum_local_kranges(_ptr(a), C.byref(sa), _ptr(b), C.byref(sb), arr, n, C.byref(so), _stream()))
+    return outs
+
+
 PATH_GENERIC, PATH_MFMA, PATH_COMPONENTWISE = 0, 1, 2
 
 

@@ -359,6 +359,39 @@ extern "C" int mtf_einsum_local(const void* a, const mtf_shape* a_local, const v
                         epi, aux, alpha, accumulate, s);
 }
 
+extern "C" int mtf_einsum_local_kranges(const void* a, const mtf_shape* a_local, const void* b,
+                                        const mtf_shape* b_local, void* const* outs, int32_t n,
+                                        const mtf_shape* out_local, void* stream) {
+  if (!outs) return fail(MTF_ERR_NULL, "outs");
+  if (n < 1 || n > kMaxGroup) return fail(MTF_ERR_UNSUPPORTED, "%d ranges (1..%d)", n, kMaxGroup);
+  for (int i = 0; i < n; ++i) {
+    if (!outs[i]) return fail(MTF_ERR_NULL, "out %d", i);
+    if (!aligned16(outs[i])) return fail(MTF_ERR_ALIGN, "out %d", i);
+  }
+  EinsumRoute r;
+  if (int rc = route_einsum(a, a_local, b, b_local, outs[0], out_local, MTF_BF16, MTF_F32, MTF_EPI_NONE, nullptr,
+                            1.f, 0, &r))
+    return rc;
+  GemmDesc& d = r.gemm;
+  if (!r.use_gemm || d.batch0 * d.batch1 != 1)
+    return fail(MTF_ERR_UNSUPPORTED, "not a plain matrix product of bf16 operands");
+  const int64_t K = d.K[0];
+  if (K % (8 * (int64_t)n)) return fail(MTF_ERR_UNSUPPORTED, "contracted size %lld not divisible by 8 x %d", (long long)K, n);
+  const int64_t kr = K / n;
+  const bf16_t *a0 = d.A[0], *b0 = d.B[0];
+  d.K[0] = kr;
+  for (int i = 1; i < n; ++i) {
+    GemmDesc::Extra& e = d.extra[d.nextra++];
+    e.A[0] = a0 + (d.a_kcontig ? i * kr : i * kr * d.lda);
+    e.B[0] = b0 + (d.b_kcontig ? i * kr : i * kr * d.ldb);
+    e.K[0] = kr;
+    e.C = outs[i];
+    e.M = d.M; e.N = d.N;
+    e.lda = d.lda; e.ldb = d.ldb; e.ldc = d.ldc;
+  }
+  return gemm_bf16_launch(d, static_cast<hipStream_t>(stream));
+}
+
 extern "C" int mtf_einsum_local_path(const void* a, const mtf_shape* a_local, const void* b,
                                      const mtf_shape* b_local, void* out, const mtf_shape* out_local,
                                      mtf_dtype in_dt, mtf_dtype out_dt, mtf_epilogue epi,

@@ -189,3 +189,43 @@ def test_run_to_run_bitwise_determinism():
     a, b = _rand("mk", torch.bfloat16, 14), _rand("kn", torch.bfloat16, 15)
     outs = [mtf.einsum_local(a.cuda(), "mk", b.cuda(), "kn", "mn", out_dtype=torch.float32).cpu() for _ in range(3)]
     assert torch.equal(outs[0], outs[1]) and torch.equal(outs[0], outs[2])
+
+
+@pytest.mark.parametrize("n", [1, 2, 4])
+@pytest.mark.parametrize("name,da,db,do", GEMM_CASES[:5] + [GEMM_CASES[7]])
+def test_contracted_dim_cut_into_ranges(name, da, db, do, n):
+    """mtf_einsum_local_kranges: range i of the contracted dim against the oracle's einsum of the
+    operands sliced to that range, the ranges' sum against the whole einsum, and exactness on
+    integers."""
+    print(f"einsum_local_kranges {name} n={n}", flush=True)
+    sizes = dict(SIZES, k=192, h=2)                    # contracted size 192 (384 when h folds in): divisible by 8 n
+    a, b = _rand(da, torch.bfloat16, 21, sizes), _rand(db, torch.bfloat16, 22, sizes)
+    parts = mtf.einsum_local_kranges(a.cuda(), da, b.cuda(), db, do, n)
+    assert len(parts) == n and all(p.dtype == torch.float32 for p in parts)
+    ins = [named(a, da), named(b, db)]
+    ref, ref_abs = einsum(ins, do), einsum_abs(ins, do)
+    total = sum(f64(p) for p in parts)
+    assert m1(total, ref.data, ref_abs.data) <= 1e-5 and m2(total, ref.data) <= BF16_TOL
+    if "h" not in da:                                  # one contracted dim: range i is a slice of k
+        kr = sizes["k"] // n
+        for i, p in enumerate(parts):
+            cut = lambda t, dims: NT(np.take(t.data, range(i * kr, (i + 1) * kr), axis=dims.index("k")), t.dims)
+            want = einsum([cut(ins[0], da), cut(ins[1], db)], do)
+            assert m2(f64(p), want.data) <= BF16_TOL, i
+    ai, bi = _rand(da, torch.bfloat16, 23, sizes, ints=True), _rand(db, torch.bfloat16, 24, sizes, ints=True)
+    parts = mtf.einsum_local_kranges(ai.cuda(), da, bi.cuda(), db, do, n)
+    assert np.array_equal(sum(f64(p) for p in parts), einsum([named(ai, da), named(bi, db)], do).data)
+
+
+def test_ranges_refused():
+    a, b = _rand("mk", torch.bfloat16, 25), _rand("kn", torch.bfloat16, 26)        # k = 200
+    with pytest.raises(mtf.MtfError) as e:
+        mtf.einsum_local_kranges(a.cuda(), "mk", b.cuda(), "kn", "mn", 4)          # 200 % 32 != 0
+    assert e.value.name == "MTF_ERR_UNSUPPORTED"
+    with pytest.raises(mtf.MtfError) as e:
+        mtf.einsum_local_kranges(a.cuda(), "mk", b.cuda(), "kn", "mn", 5)
+    assert e.value.name == "MTF_ERR_UNSUPPORTED"
+    ab, bb = _rand("bmk", torch.bfloat16, 27, dict(SIZES, k=192)), _rand("bkn", torch.bfloat16, 28, dict(SIZES, k=192))
+    with pytest.raises(mtf.MtfError) as e:
+        mtf.einsum_local_kranges(ab.cuda(), "bmk", bb.cuda(), "bkn", "bmn", 2)     # batch dims: not this call
+    assert e.value.name == "MTF_ERR_UNSUPPORTED"

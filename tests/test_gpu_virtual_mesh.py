@@ -130,8 +130,9 @@ def _mesh3d_tools(g, mesh, layout, coords):
     sl = lambda name, dims: {c: mtf.slice_copy(g[name], dims, mesh, layout, c) for c in coords}
     # epi / aux: a component-wise operation riding on the reduce (aux per processor)
     reduced = lambda parts, ax, dtype, epi=mtf.EPI_NONE, aux=None: {
-        c: mtf.reduce_partials([parts[c2] for c2 in group(c, ax)], out_dtype=dtype, epi=epi,
-                               aux=None if aux is None else aux[c]) for c in coords}
+        c: mtf.reduce_partials([t for c2 in group(c, ax) for t in (parts[c2] if isinstance(parts[c2], list)
+                                                                      else [parts[c2]])],
+                               out_dtype=dtype, epi=epi, aux=None if aux is None else aux[c]) for c in coords}
     return axes, sl, reduced
 
 
@@ -150,8 +151,10 @@ def _mesh3d_forward(g, mesh, layout, coords, fused=False):
     else:
         h = reduced(h_parts, ax_h, torch.bfloat16)
         a = {c: mtf.einsum_local(h[c], HID, None, None, HID, epi=mtf.EPI_RELU) for c in coords}
-    y = reduced({c: mtf.einsum_local(a[c], HID, wo[c], WO, X, out_dtype=torch.float32) for c in coords}, ax_y,
-                torch.float32)
+    # fused: the narrow einsums also run as two ranges of their contracted dim (mtf_einsum_local_kranges)
+    es = (lambda p, pd, q, qd, od: mtf.einsum_local_kranges(p, pd, q, qd, od, 2)) if fused else \
+        (lambda p, pd, q, qd, od: mtf.einsum_local(p, pd, q, qd, od, out_dtype=torch.float32))
+    y = reduced({c: es(a[c], HID, wo[c], WO, X) for c in coords}, ax_y, torch.float32)
     return dict(a=a, y=y)
 
 
@@ -162,8 +165,9 @@ def _mesh3d_backward(g, mesh, layout, coords, a, fused=False):
     ax_dwo, ax_da, ax_dwi, ax_dx = axes(HID, X, WO), axes(X, WO, HID), axes(X, HID, WI), axes(HID, WI, X)
     assert ax_dwo == [0] and ax_da == [2] and ax_dwi == [0] and ax_dx == [1]   # rows, planes, rows, cols
     out = {}
-    out["dw_out"] = reduced({c: mtf.einsum_local(a[c], HID, dys[c], X, WO, out_dtype=torch.float32) for c in coords},
-                            ax_dwo, torch.float32)
+    es = (lambda p, pd, q, qd, od: mtf.einsum_local_kranges(p, pd, q, qd, od, 2)) if fused else \
+        (lambda p, pd, q, qd, od: mtf.einsum_local(p, pd, q, qd, od, out_dtype=torch.float32))
+    out["dw_out"] = reduced({c: es(a[c], HID, dys[c], X, WO) for c in coords}, ax_dwo, torch.float32)
     da_parts = {c: mtf.einsum_local(dys[c], X, wo[c], WO, HID, out_dtype=torch.float32) for c in coords}
     if fused:
         dh = reduced(da_parts, ax_da, torch.bfloat16, mtf.EPI_MASK_GT0, a)
@@ -171,10 +175,8 @@ def _mesh3d_backward(g, mesh, layout, coords, a, fused=False):
         da = reduced(da_parts, ax_da, torch.bfloat16)
         dh = {c: mtf.einsum_local(da[c], HID, None, None, HID, epi=mtf.EPI_MASK_GT0, aux=a[c]) for c in coords}
     out["dh"] = dh
-    out["dw_in"] = reduced({c: mtf.einsum_local(xs[c], X, dh[c], HID, WI, out_dtype=torch.float32) for c in coords},
-                           ax_dwi, torch.float32)
-    out["dx"] = reduced({c: mtf.einsum_local(dh[c], HID, wi[c], WI, X, out_dtype=torch.float32) for c in coords},
-                        ax_dx, torch.float32)
+    out["dw_in"] = reduced({c: es(xs[c], X, dh[c], HID, WI) for c in coords}, ax_dwi, torch.float32)
+    out["dx"] = reduced({c: es(dh[c], HID, wi[c], WI, X) for c in coords}, ax_dx, torch.float32)
     return out
 
 
@@ -217,14 +219,18 @@ def test_three_dimensional_layout_at_shard_size_bf16():
             err = m2(f64(got[k][c]), want.data)
             assert err <= BF16_TOL, (k, c, err)
     print("3-D layout: all slices within tolerance", flush=True)
-    # the ReLU and its gradient mask applied by the reduce that completes the sum: the same bits
-    print("3-D layout: component-wise operations fused into the reduces", flush=True)
+    # the ReLU and its gradient mask applied by the reduce that completes the sum: the same bits;
+    # the narrow einsums as two ranges of their contracted dim: another summation order, same bound
+    print("3-D layout: component-wise operations fused into the reduces, narrow einsums in ranges", flush=True)
     fwd2 = _mesh3d_forward(g, mesh, layout, coords, fused=True)
     got2 = _mesh3d_backward(g, mesh, layout, coords, a_ref, fused=True)
     for c in coords:
-        assert torch.equal(fwd2["a"][c], fwd["a"][c]) and torch.equal(fwd2["y"][c], fwd["y"][c]), c
-        for k in ("dh", "dw_in", "dw_out", "dx"):
-            assert torch.equal(got2[k][c], got[k][c]), (k, c)
+        assert torch.equal(fwd2["a"][c], fwd["a"][c]) and torch.equal(got2["dh"][c], got["dh"][c]), c
+        err = m2(f64(fwd2["y"][c]), OLY.slice_tensor(ref["y"], mesh, layout, c).data)
+        assert err <= BF16_TOL, ("y", c, err)
+        for k in ("dw_in", "dw_out", "dx"):
+            err = m2(f64(got2[k][c]), OLY.slice_tensor(refb[k], mesh, layout, c).data)
+            assert err <= BF16_TOL, (k, c, err)
 
 
 def to_dev_bf16(arr):

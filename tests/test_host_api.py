@@ -146,6 +146,8 @@ def test_argument_validation_needs_no_gpu():
     assert lib.mtf_reduce_partials_epi(one, 1, None, 0, p, 0, C.c_int64(8), 3, None, None) == -10   # no such epilogue here
     assert lib.mtf_reduce_partials_epi(one, 1, None, 0, p, 0, C.c_int64(8), 2, None, None) == -1    # mask without aux
     assert lib.mtf_reduce_partials_epi(one, 1, None, 0, p, 0, C.c_int64(8), 2, C.c_void_p(4098), None) == -14
+    assert lib.mtf_einsum_local_kranges(p, None, p, None, None, 2, None, None) == -1                 # outs NULL
+    assert lib.mtf_einsum_local_kranges(p, None, p, None, one, 5, None, None) == -10                # at most 4 ranges
     # the worked example with its bias, broadcasting addition, local reduction
     assert lib.mtf_ffn_bias_fwd(C.byref(d), p, p, None, p, p, p, None) == -1                     # bias NULL
     assert lib.mtf_ffn_bias_bwd(C.byref(d), p, p, p, p, p, p, p, p, p, None, C.c_size_t(0), None) == -11
