@@ -20,8 +20,10 @@ pytestmark = pytest.mark.gpu
 X, WI, WO, HID = (B, L, D), (D, F), (F, D), (B, L, F)
 
 
-def _virtual_mesh_ffn(g, mesh, layout, fp32):
-    """Returns {coord: y after the grouped reduce} computed slice by slice on the device."""
+def _virtual_mesh_ffn(g, mesh, layout, fp32, kranges=0):
+    """Returns {coord: y after the grouped reduce} computed slice by slice on the device.
+    kranges > 0: the second einsum of every slice as that many ranges of d_ff; their sums all go
+    into the group's reduce."""
     shp = lambda t, dims: list(zip(dims, t.shape))
     plan = mtf.einsum_plan(shp(g["x"], X)[:2] + [(F, g["w_in"].shape[1])], shp(g["w_out"], WO),
                            shp(g["x"], X), mesh, layout)
@@ -33,14 +35,17 @@ def _virtual_mesh_ffn(g, mesh, layout, fp32):
         wo = mtf.slice_copy(g["w_out"], WO, mesh, layout, c)
         if fp32:
             h = mtf.einsum_local(xs, X, wi, WI, HID, epi=mtf.EPI_RELU)
-            partial[c] = mtf.einsum_local(h, HID, wo, WO, X)
+            partial[c] = [mtf.einsum_local(h, HID, wo, WO, X)]
+        elif kranges:
+            h = mtf.einsum_local(xs, X, wi, WI, HID, epi=mtf.EPI_RELU)
+            partial[c] = mtf.einsum_local_kranges(h, HID, wo, WO, X, kranges)
         else:
-            partial[c] = mtf.ffn_fwd(xs, wi, wo)[1]
+            partial[c] = [mtf.ffn_fwd(xs, wi, wo)[1]]
     out = {}
     for c in OLY.all_coords(mesh):
         group = [c2 for c2 in OLY.all_coords(mesh)
                  if all(c2[i] == c[i] for i in range(len(mesh)) if i not in axes)]
-        out[c] = mtf.reduce_partials([partial[c2] for c2 in group])
+        out[c] = mtf.reduce_partials([t for c2 in group for t in partial[c2]])
     return out, axes
 
 
@@ -100,6 +105,12 @@ def test_config4_virtual_4x4_mesh_full_size():
     # against the oracle on sampled tokens (a feed-forward output row depends on its own input row
     # only): after the reduce every processor of a mesh row holds that row's complete y, so each
     # sampled token is checked on all four processors (mesh columns) of its row
+    # the second einsum of every slice as two ranges of d_ff (mtf_einsum_local_kranges), eight range
+    # sums per group: same products, another summation order
+    print("config 4: 16 slices, second einsum in two ranges", flush=True)
+    out2, _ = _virtual_mesh_ffn(g, mesh, layout, fp32=False, kranges=2)
+    for c, y in out2.items():
+        assert m2(f64(y), f64(out[c])) <= 1e-4, c
     print("config 4: oracle on sampled tokens, every mesh column", flush=True)
     rng = np.random.default_rng(4)
     w_in, w_out = named(cfg["w_in"], WI), named(cfg["w_out"], WO)
