@@ -346,9 +346,14 @@ int mtf_mha_fwd(const mtf_mha_dims* d, const void* x, const void* w_q, const voi
   return rc < 0 ? rc : MTF_OK;
 }
 
+// Ranges the attention sublayer's dx is cut into when it is called on its own (the whole-layer
+// step has its own partial-sum buffers): 4 give a 2048-token shard 512 small tiles.
+constexpr int kMhaDxRanges = 4;
+
 size_t mtf_mha_bwd_workspace_bytes(const mtf_mha_dims* d) {
-  if (!d || d->batch <= 0 || d->length <= 0 || d->heads <= 0 || d->d_k <= 0) return 0;
-  return mha_bwd_scratch(d, nullptr).bytes;
+  if (!d || d->batch <= 0 || d->length <= 0 || d->heads <= 0 || d->d_k <= 0 || d->d_model <= 0) return 0;
+  return mha_bwd_scratch(d, nullptr).bytes +
+         kMhaDxRanges * round256((size_t)d->batch * d->length * d->d_model * 4);
 }
 
 int mtf_mha_bwd(const mtf_mha_dims* d, const void* x, const void* w_q, const void* w_k,
@@ -362,9 +367,19 @@ int mtf_mha_bwd(const mtf_mha_dims* d, const void* x, const void* w_q, const voi
     return rc;
   if (!workspace || workspace_bytes < mtf_mha_bwd_workspace_bytes(d) || !aligned16(workspace))
     return fail(MTF_ERR_WORKSPACE, "mtf_mha_bwd needs %zu bytes", mtf_mha_bwd_workspace_bytes(d));
-  const int rc = mha_bwd(d, x, w_q, w_k, w_v, w_o, q, k, v, ctx, lse, dy, scale, causal, dw_q, dw_k, dw_v, dw_o,
-                         single(dx_partial), mha_bwd_scratch(d, workspace), static_cast<hipStream_t>(stream));
-  return rc < 0 ? rc : MTF_OK;
+  // dx as kMhaDxRanges ranges of its contracted axis (so that a small shard still fills the CUs),
+  // summed into dx_partial by the reduce; shapes that cannot be cut write dx_partial directly
+  const MhaBwdScratch scratch = mha_bwd_scratch(d, workspace);
+  const int64_t count = d->batch * d->length * d->d_model;
+  Partials parts = carve(static_cast<char*>(workspace) + scratch.bytes, kMhaDxRanges, count);
+  const bool cut = (3 * d->heads * d->d_k) % (8 * kMhaDxRanges) == 0;
+  if (!cut) parts = single(dx_partial);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const int n = mha_bwd(d, x, w_q, w_k, w_v, w_o, q, k, v, ctx, lse, dy, scale, causal, dw_q, dw_k, dw_v, dw_o,
+                        parts, scratch, s);
+  if (n < 0) return n;
+  if (!cut) return MTF_OK;
+  return mtf_reduce_partials(parts.buf, n, nullptr, MTF_F32, dx_partial, MTF_F32, count, s);
 }
 
 static int check_layer(const mtf_layer_dims* d, mtf_ffn_dims* f, mtf_mha_dims* m) {
@@ -416,7 +431,7 @@ size_t mtf_layer_bwd_workspace_bytes(const mtf_layer_dims* d) {
   m = mtf_mha_dims{d->batch, d->length, d->d_model, d->heads, d->d_k};
   const size_t partial = kLayerPartials * round256((size_t)d->batch * d->length * d->d_model * 4);
   const size_t du = round256((size_t)d->batch * d->length * d->d_model * 2);
-  return partial + du + std::max(mtf_ffn_bwd_workspace_bytes(&f), mtf_mha_bwd_workspace_bytes(&m));
+  return partial + du + std::max(mtf_ffn_bwd_workspace_bytes(&f), mha_bwd_scratch(&m, nullptr).bytes);
 }
 
 int mtf_layer_bwd(const mtf_layer_dims* d, const void* x, const mtf_layer_weights* w,
