@@ -26,7 +26,7 @@
  *     machine without one.
  *
  * Contents: slices and lowering plans (host); slice gather, the local einsum with its fused
- * epilogues, partial-sum reduce (the Allreduce stand-in on a virtual mesh; also with a
+ * epilogues (also cut into ranges of its contracted dim), partial-sum reduce (the Allreduce stand-in on a virtual mesh; also with a
  * component-wise epilogue), the data-parallel
  * training step; component-wise
  * addition with implicit broadcasting, local reductions; reshape on a virtual mesh (renaming,
