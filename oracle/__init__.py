@@ -17,7 +17,8 @@ Modules
   norm     layer normalisation over d_model (two reductions + component-wise operations),
            forward and backward, alone and after the residual sum
   optim    the step of synchronous data-parallel training with replicated parameters
-           (Algorithm 1): sum of the processors' gradients, gradient-descent update
+           (Algorithm 1): sum of the processors' gradients, gradient-descent update; the
+           Allreduce point followed by a component-wise operation
   metrics  the error measures the parity tests gate on
 
 Pins (see tests/test_oracle_*.py): brute-force loops on tiny inputs, closed forms

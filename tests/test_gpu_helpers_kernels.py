@@ -6,6 +6,8 @@ import torch
 
 import paper_1811_02084_amd as mtf
 from oracle import layout as OLY
+from oracle import optim as OO
+from oracle.layer import identity
 from oracle.bf16 import f64_to_bf16_bits
 from oracle.einsum import NT
 from oracle.metrics import m2
@@ -85,19 +87,18 @@ def test_reduce_partials_with_a_componentwise_epilogue(n, count):
     rng = np.random.default_rng(n * 7919 + count)
     parts = [rng.standard_normal(count).astype(np.float32) for _ in range(n)]
     dparts = [torch.from_numpy(p).cuda() for p in parts]
-    total = sum(p.astype(np.float64) for p in parts)
     aux = rng.standard_normal(count).astype(np.float32)
     aux[::5] = 0.0                                   # exactly zero: gradient 0 there
     aux[1::11] = -0.0
     daux = torch.from_numpy(aux).to(torch.bfloat16).cuda()
-    visible = daux.float().cpu().numpy() > 0.0
-    dims = [("i", count)]
+    aux_stored = daux.float().cpu().numpy()
+    visible = aux_stored > 0.0
     for dt, tol in ((torch.float32, F32_TOL), (torch.bfloat16, 2.0 ** -8)):
         got = mtf.reduce_partials(dparts, out_dtype=dt, epi=mtf.EPI_RELU)
-        assert m2(f64(got), np.maximum(total, 0.0)) <= tol
+        assert m2(f64(got), OO.allreduce_then(parts, op="relu", store=identity)) <= tol
         assert not bool((got.float() < 0).any())
         got = mtf.reduce_partials(dparts, out_dtype=dt, epi=mtf.EPI_MASK_GT0, aux=daux)
-        assert m2(f64(got), np.where(visible, total, 0.0)) <= tol
+        assert m2(f64(got), OO.allreduce_then(parts, op="mask", aux=aux_stored, store=identity)) <= tol
         assert not bool(got.float()[torch.from_numpy(~visible).cuda()].any())
     if count % 8 == 0:                               # the component-wise path of the einsum call takes whole vectors
         plain = mtf.reduce_partials(dparts, out_dtype=torch.bfloat16)
@@ -108,11 +109,12 @@ def test_reduce_partials_with_a_componentwise_epilogue(n, count):
                            two_pass)
     ints = [rng.integers(-8, 9, count).astype(np.float32) for _ in range(n)]
     got = mtf.reduce_partials([torch.from_numpy(p).cuda() for p in ints], epi=mtf.EPI_RELU)
-    assert np.array_equal(got.cpu().numpy(), np.maximum(sum(ints), 0))
+    assert np.array_equal(got.cpu().numpy(), OO.allreduce_then(ints, op="relu", store=identity))
     res = torch.from_numpy(rng.integers(-8, 9, count).astype(np.float32)).to(torch.bfloat16)
     got = mtf.reduce_partials([torch.from_numpy(p).cuda() for p in ints], residual=res.cuda(), out_dtype=torch.float32,
                               epi=mtf.EPI_MASK_GT0, aux=daux)
-    assert np.array_equal(got.cpu().numpy(), np.where(visible, sum(ints) + res.float().numpy(), 0))
+    assert np.array_equal(got.cpu().numpy(), OO.allreduce_then(ints, residual=res.float().numpy(), op="mask",
+                                                              aux=aux_stored, store=identity))
 
 
 def test_cast_rounds_to_nearest_even_bit_exact():

@@ -45,3 +45,30 @@ def test_sub_batch_gradients_add_up_to_the_batch_gradient():
         assert np.allclose(OO.allreduce_sum(parts[k]), full[k].data, rtol=0, atol=1e-12)
         stepped, _ = OO.sgd_step(w.data, parts[k], 0.1, identity)
         assert np.allclose(stepped, w.data - 0.1 * full[k].data, rtol=0, atol=1e-12)
+
+
+def test_allreduce_point_with_a_componentwise_operation_worked_by_hand():
+    parts = [np.array([1.0, -2.0, 0.5, -0.25]), np.array([0.5, 1.0, -0.5, -0.25])]      # sum: 1.5, -1, 0, -0.5
+    assert OO.allreduce_then(parts, store=identity).tolist() == [1.5, -1.0, 0.0, -0.5]
+    assert OO.allreduce_then(parts, op="relu", store=identity).tolist() == [1.5, 0.0, 0.0, 0.0]
+    # the ReLU gradient: the sum passes where the saved activation is > 0 (0 and -0 block it)
+    aux = np.array([2.0, 3.0, 0.0, -0.0])
+    assert OO.allreduce_then(parts, op="mask", aux=aux, store=identity).tolist() == [1.5, -1.0, 0.0, 0.0]
+    res = np.array([-2.0, 2.0, 1.0, 1.0])
+    assert OO.allreduce_then(parts, residual=res, op="relu", store=identity).tolist() == [0.0, 1.0, 1.0, 0.5]
+    # relu(sum) is not the sum of relus: the operation follows the Allreduce
+    assert OO.allreduce_then(parts, op="relu", store=identity).tolist() != \
+        (np.maximum(parts[0], 0) + np.maximum(parts[1], 0)).tolist()
+    # storage rounding applies to the result: 1 + 2^-9 rounds to 1 in bfloat16
+    assert OO.allreduce_then([np.array([1.0]), np.array([2.0 ** -9])])[0] == 1.0
+    # the worked example on the 3-D layout: relu of the Allreduce over the d_model split equals the
+    # unsplit hidden layer
+    mesh, layout = [("planes", 2)], [("d_model", "planes")]
+    x = nt(RNG.standard_normal((2, 3, 8)), (B, L, D))
+    w_in = nt(RNG.standard_normal((8, 5)), (D, F))
+    from oracle.einsum import einsum
+    hs = [einsum([slice_tensor(x, mesh, layout, c), slice_tensor(w_in, mesh, layout, c)], (B, L, F)).data
+          for c in all_coords(mesh)]
+    want = np.maximum(einsum([x, w_in], (B, L, F)).data, 0.0)
+    assert np.allclose(OO.allreduce_then(hs, op="relu", store=identity), want, rtol=0, atol=1e-13)
+
